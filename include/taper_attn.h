@@ -1,0 +1,226 @@
+/*
+ * taper_attn -- decode-step attention over a paged bf16 KV cache whose parallel
+ * branches share their request's prefix pages (MI355X / gfx950).
+ *
+ * One decode step is one forward pass that advances every admitted sequence by
+ * one token (paper §1, §2.3).  A sequence is a serial request or one admitted
+ * branch of a request in a parallel phase.  By the visibility rule (paper §3.1)
+ * a branch token attends to the request's shared prefix followed by the branch's
+ * own private tokens and to nothing of its siblings; the shared prefix is stored
+ * once and served to all branches "from a single set of prefix blocks" (§3.1),
+ * a branch materialising only its branch-local tokens (App. C, memory
+ * accounting).  The time this call takes is the attention term of the step
+ * latency T(S) that the admission controller budgets against (§3.2, App. C).
+ *
+ * All entry points are plain C.  "host" / "device" after a pointer says where the
+ * memory must live.  Every function returns 0 on success or a negative
+ * taper_status; none throws or aborts.  taper_last_error() gives a message for
+ * the calling thread's last failure.
+ *
+ * ---------------------------------------------------------------- data layout
+ * q, out : bf16 [n_seqs][n_q_heads][head_dim], row-major, device.
+ * lse    : f32  [n_seqs][n_q_heads], device (optional): natural-log normaliser
+ *          log sum_t exp(scale * q.k_t).
+ * kv_pages (the pool), device: bf16 [n_pool_pages][2][n_kv_heads][page_size*head_dim];
+ *          index 0 of the second axis is K, 1 is V.  Inside one
+ *          (page, K, kv head) tile, element (tok, d) is at
+ *                (d / 8) * (page_size * 8) + tok * 8 + d % 8
+ *          i.e. K is stored in groups of 8 dims: [head_dim/8][page_size][8].
+ *          Inside one (page, V, kv head) tile, element (tok, d) is at
+ *                (tok / 4) * (4 * head_dim) + d * 4 + tok % 4
+ *          i.e. V is stored transposed in groups of 4 tokens: [page_size/4][head_dim][4].
+ *          Both are what a 64-lane MFMA operand fetch reads with unit stride.
+ *          Slots past a segment's length and unreferenced pages may hold any
+ *          finite values; results do not depend on them.
+ * Grouped-query attention: query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *
+ * ---------------------------------------------------------------- the batch
+ * block_table[s][*] (int32, host, row stride bt_row_stride): the physical pages
+ *   of sequence s in logical order: first ceil(prefix_len[s]/page_size) entries
+ *   are the request's shared prefix pages (identical for all members of a
+ *   request), then ceil(suffix_len[s]/page_size) private pages.  Private tokens
+ *   start on a fresh page even if the prefix ends mid-page.
+ * branch_group[s] (int32, host): request id; starts at 0, non-decreasing in steps
+ *   of 1, members of one request contiguous.
+ * prefix_len[s], suffix_len[s] (int32, host): shared and private token counts
+ *   (P ++ H and h_i ++ y_{i,<t} of §3.1).  prefix_len is equal inside a request.
+ *   A serial request is a group of one; its context may be given as prefix,
+ *   suffix or both.  prefix_len + suffix_len >= 1.
+ */
+#ifndef TAPER_ATTN_H
+#define TAPER_ATTN_H
+
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define TAPER_API __attribute__((visibility("default")))
+#else
+#define TAPER_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TAPER_OK = 0,
+    TAPER_EINVAL = -1, /* null pointer, unsupported shape, bad argument            */
+    TAPER_EBLOCK = -2, /* block-table entry < 0 or >= n_pool_pages                 */
+    TAPER_EGROUP = -3, /* group ids not contiguous / prefix differs inside a group */
+    TAPER_ELEN = -4,   /* negative length, empty context, row too short            */
+    TAPER_EHIP = -5,   /* HIP runtime error, or a device call on a host-only ctx   */
+    TAPER_ENOMEM = -6  /* host or device allocation failed                         */
+} taper_status;
+
+typedef struct {
+    int n_q_heads;  /* 64 (Qwen3-32B shape, App. D) or any multiple of n_kv_heads  */
+    int n_kv_heads; /* 8                                                            */
+    int head_dim;   /* 64 or 128                                                    */
+    int page_size;  /* 16                                                           */
+    float scale;    /* softmax scale, normally 1/sqrt(head_dim)                     */
+    int device;     /* HIP device ordinal; -1 = host-only context: plans can be
+                       built, validated and exported, device calls return TAPER_EHIP */
+} taper_attn_config;
+
+typedef struct taper_ctx taper_ctx;   /* owns the partials workspace              */
+typedef struct taper_plan taper_plan; /* owns host + device copies of the step's integer metadata */
+
+/* One unit of KV streaming: n_tokens tokens starting at block-table entry page0 of
+ * row seq0, multiplied against the query rows of n_branch consecutive sequences. */
+typedef struct {
+    int32_t seq0;      /* first sequence; its block-table row supplies the pages    */
+    int32_t n_branch;  /* sequences seq0..seq0+n_branch-1 share these tokens        */
+    int32_t page0;     /* first block-table entry of the chunk                      */
+    int32_t n_tokens;  /* valid tokens in the chunk (>= 1)                          */
+    int32_t part_base; /* first partial row; row of (kv head hk, branch b, head-in-group j)
+                          = part_base + hk * n_branch * gqa + b * gqa + j           */
+    int32_t kind;      /* 0 = shared prefix of a parallel request, 1 = private      */
+    int32_t part;      /* workgroup share this item belongs to                      */
+    int32_t reserved;
+} taper_work_item;
+
+/* Where sequence s finds one of its partials: rows first_row + hk*rows_per_head + j */
+typedef struct {
+    int32_t first_row;
+    int32_t rows_per_head;
+} taper_merge_entry;
+
+/* Read-only view of a plan's host-side integers (valid until taper_plan_free). */
+typedef struct {
+    int32_t n_seqs, n_groups;
+    const int32_t *ctx_len;        /* [n_seqs] prefix_len + suffix_len                      */
+    const int32_t *n_prefix_pages; /* [n_seqs] ceil(prefix_len / page_size)                 */
+    const int32_t *n_suffix_pages; /* [n_seqs] ceil(suffix_len / page_size): the branch's
+                                      marginal blocks (App. C), 0 for an empty branch       */
+    const int32_t *group_start;    /* [n_groups + 1] CSR of requests over sequences         */
+    int32_t n_items;
+    const taper_work_item *items;  /* [n_items], ordered by part                            */
+    int32_t n_parts_shared, n_parts_private;
+    const int32_t *part_start;     /* [n_parts_shared + n_parts_private + 1] CSR over items */
+    const int32_t *merge_start;    /* [n_seqs + 1] CSR over merge entries                   */
+    const taper_merge_entry *merge;
+    int64_t n_partial_rows;
+    int64_t tokens_unique;  /* sum over requests of prefix_len + sum over sequences of suffix_len */
+    int64_t tokens_logical; /* sum over sequences of prefix_len + suffix_len: L_context of §3.2   */
+} taper_plan_view;
+
+typedef struct {
+    int32_t target_workgroups; /* 0 = default; workgroup shares the KV stream is cut into */
+    int32_t share_prefix;      /* 1 = default: read each request's prefix once for all its
+                                  branches; 0 = every branch streams the prefix by itself  */
+    int32_t max_branches_per_item; /* 0 = default (24); wider requests are cut into sub-groups */
+    int32_t reserved;
+} taper_plan_options;
+
+TAPER_API int taper_create(const taper_attn_config *cfg /* host */, taper_ctx **out_ctx);
+TAPER_API void taper_destroy(taper_ctx *ctx);
+
+/*
+ * Index resolution for one decode step (paper: the engine's batch formation
+ * precedes the forward pass, App. D "Serving engine"; which pages each query row
+ * reads follows §3.1).  Validates the batch, derives the request CSR, page counts,
+ * the list of KV chunks and the merge map, copies them to the device on
+ * `hip_stream` (unless the context is host-only) and grows the context's
+ * workspace if needed.  The host arrays are only read during the call.  One plan
+ * serves every layer of the step.  Not safe to call concurrently on one ctx.
+ * opts may be NULL.
+ */
+TAPER_API int taper_plan_build(taper_ctx *ctx, int n_seqs, const int32_t *block_table /* host */, int bt_row_stride,
+                     const int32_t *branch_group /* host */, const int32_t *prefix_len /* host */,
+                     const int32_t *suffix_len /* host */, int64_t n_pool_pages,
+                     const taper_plan_options *opts /* host, may be NULL */, void *hip_stream,
+                     taper_plan **out_plan);
+TAPER_API void taper_plan_free(taper_plan *plan);
+TAPER_API int taper_plan_export(const taper_plan *plan, taper_plan_view *out_view /* host */);
+
+/*
+ * Physical slot id (page * page_size + token-in-page) of every logical position:
+ * slots[s * stride + t] for t < ctx_len[s], -1 after.  The host form reads the
+ * plan's host copy; the device form runs a kernel over the very device arrays the
+ * attention kernels index with, and writes `slots` in device memory.
+ */
+TAPER_API int taper_plan_resolve_slots_host(const taper_plan *plan, int64_t *slots /* host */, int64_t stride);
+TAPER_API int taper_plan_resolve_slots(taper_ctx *ctx, const taper_plan *plan, int64_t *slots /* device */, int64_t stride,
+                             void *hip_stream);
+
+/*
+ * The hot call (paper §1/§2.3 decode step; §3.1 visibility rule): for every
+ * sequence s and query head h,
+ *     out[s,h,:] = sum_t softmax_t(scale * q[s,h,:].K_t) V_t
+ * over t in shared prefix ++ private tokens of s.  Enqueues kernels on
+ * `hip_stream` and returns; allocates nothing, does not synchronise.  q, kv_pages,
+ * out (and lse if not NULL) are device pointers owned by the caller and must stay
+ * valid until the stream has run the work.  Calls on one ctx share its workspace
+ * and must be ordered on one stream.
+ */
+TAPER_API int taper_decode_step_attention(taper_ctx *ctx, const taper_plan *plan, const void *q /* device */,
+                                const void *kv_pages /* device */, void *out /* device */,
+                                float *lse /* device, may be NULL */, void *hip_stream);
+
+/* Same operation with the batch arrays passed directly: builds a transient plan,
+ * runs the step and frees the plan after synchronising the stream. */
+TAPER_API int taper_decode_step_attention_simple(taper_ctx *ctx, int n_seqs, const void *q /* device */,
+                                       const void *kv_pages /* device */, int64_t n_pool_pages,
+                                       const int32_t *block_table /* host */, int bt_row_stride,
+                                       const int32_t *branch_group /* host */, const int32_t *prefix_len /* host */,
+                                       const int32_t *suffix_len /* host */, void *out /* device */,
+                                       void *hip_stream);
+
+/*
+ * Step-latency probe (paper App. C "Fitting": wall-clock latency of synthetic
+ * steps; §2.3: externality E = T(S(k)) - T(S0)).  Runs `warmup` untimed and
+ * `iters` timed steps; a step enqueues the attention of n_layers layers (layer l
+ * uses q[l], kv[l], out[l]) with one plan.  Each step is bracketed by HIP events
+ * on `hip_stream`.  The call synchronises the stream.
+ */
+typedef struct {
+    double us_min, us_median, us_mean; /* per step (all layers)                       */
+    int32_t n_tokens;                  /* sequences in the step (n_tokens of App. C)  */
+    int32_t n_layers;
+    int64_t l_context;                 /* aggregate context length (L_context)        */
+    int64_t kv_bytes_unique;           /* per layer, prefix counted once per request  */
+    int64_t kv_bytes_logical;          /* per layer, prefix counted once per sequence */
+    double gbps_unique, gbps_logical;  /* from us_median                              */
+} taper_probe_result;
+
+TAPER_API int taper_step_latency_probe(taper_ctx *ctx, const taper_plan *plan, int n_layers,
+                             const void *const *q_per_layer /* host array of device ptrs */,
+                             const void *const *kv_per_layer /* host array of device ptrs */,
+                             void *const *out_per_layer /* host array of device ptrs */, int warmup, int iters,
+                             void *hip_stream, taper_probe_result *result /* host */);
+
+/*
+ * Per-kernel timing of one step's launches with HIP events on `hip_stream`
+ * (synchronises).  us[0] = shared-prefix kernel, us[1] = private/serial kernel,
+ * us[2] = merge kernel; mean over `iters` steps after `warmup`.
+ */
+TAPER_API int taper_kernel_times(taper_ctx *ctx, const taper_plan *plan, const void *q, const void *kv_pages, void *out,
+                       int warmup, int iters, void *hip_stream, double us[3] /* host */);
+
+TAPER_API const char *taper_strerror(int status);
+TAPER_API const char *taper_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAPER_ATTN_H */

@@ -1,0 +1,249 @@
+"""Thin ctypes binding of libtaper_attn.so: argument marshalling only.
+
+Every step of the decode-step attention runs in the HIP library; this module
+converts numpy / torch arguments to pointers and sizes.  torch is used for
+device memory and streams, nothing else.  There is no fallback: if the library
+is missing or fails to load, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libtaper_attn.so")
+
+TAPER_OK, TAPER_EINVAL, TAPER_EBLOCK, TAPER_EGROUP, TAPER_ELEN, TAPER_EHIP, TAPER_ENOMEM = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTED = [
+    "taper_create", "taper_destroy", "taper_plan_build", "taper_plan_free", "taper_plan_export",
+    "taper_plan_resolve_slots_host", "taper_plan_resolve_slots", "taper_decode_step_attention",
+    "taper_decode_step_attention_simple", "taper_step_latency_probe", "taper_kernel_times",
+    "taper_strerror", "taper_last_error",
+]
+
+
+class taper_attn_config(ctypes.Structure):
+    _fields_ = [("n_q_heads", ctypes.c_int), ("n_kv_heads", ctypes.c_int), ("head_dim", ctypes.c_int),
+                ("page_size", ctypes.c_int), ("scale", ctypes.c_float), ("device", ctypes.c_int)]
+
+
+class taper_work_item(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("seq0", "n_branch", "page0", "n_tokens", "part_base", "kind", "part", "reserved")]
+
+
+class taper_merge_entry(ctypes.Structure):
+    _fields_ = [("first_row", ctypes.c_int32), ("rows_per_head", ctypes.c_int32)]
+
+
+_I32P = ctypes.POINTER(ctypes.c_int32)
+
+
+class taper_plan_view(ctypes.Structure):
+    _fields_ = [("n_seqs", ctypes.c_int32), ("n_groups", ctypes.c_int32), ("ctx_len", _I32P),
+                ("n_prefix_pages", _I32P), ("n_suffix_pages", _I32P), ("group_start", _I32P),
+                ("n_items", ctypes.c_int32), ("items", ctypes.POINTER(taper_work_item)),
+                ("n_parts_shared", ctypes.c_int32), ("n_parts_private", ctypes.c_int32), ("part_start", _I32P),
+                ("merge_start", _I32P), ("merge", ctypes.POINTER(taper_merge_entry)),
+                ("n_partial_rows", ctypes.c_int64), ("tokens_unique", ctypes.c_int64),
+                ("tokens_logical", ctypes.c_int64)]
+
+
+class taper_plan_options(ctypes.Structure):
+    _fields_ = [("target_workgroups", ctypes.c_int32), ("share_prefix", ctypes.c_int32),
+                ("max_branches_per_item", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class taper_probe_result(ctypes.Structure):
+    _fields_ = [("us_min", ctypes.c_double), ("us_median", ctypes.c_double), ("us_mean", ctypes.c_double),
+                ("n_tokens", ctypes.c_int32), ("n_layers", ctypes.c_int32), ("l_context", ctypes.c_int64),
+                ("kv_bytes_unique", ctypes.c_int64), ("kv_bytes_logical", ctypes.c_int64),
+                ("gbps_unique", ctypes.c_double), ("gbps_logical", ctypes.c_double)]
+
+
+class TaperError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"taper_attn status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library (raises if it has not been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or paper_2605_06914_amd/build.py); there is no fallback path")
+    try:  # share torch's HIP runtime (same soname) when torch is importable
+        import torch  # noqa: F401
+    except Exception:  # pragma: no cover - torch is only needed for device work
+        pass
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    lib.taper_create.argtypes = [ctypes.POINTER(taper_attn_config), ctypes.POINTER(vp)]
+    lib.taper_destroy.argtypes = [vp]
+    lib.taper_destroy.restype = None
+    lib.taper_plan_build.argtypes = [vp, ci, vp, ci, vp, vp, vp, i64, ctypes.POINTER(taper_plan_options), vp,
+                                     ctypes.POINTER(vp)]
+    lib.taper_plan_free.argtypes = [vp]
+    lib.taper_plan_free.restype = None
+    lib.taper_plan_export.argtypes = [vp, ctypes.POINTER(taper_plan_view)]
+    lib.taper_plan_resolve_slots_host.argtypes = [vp, vp, i64]
+    lib.taper_plan_resolve_slots.argtypes = [vp, vp, vp, i64, vp]
+    lib.taper_decode_step_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.taper_decode_step_attention_simple.argtypes = [vp, ci, vp, vp, i64, vp, ci, vp, vp, vp, vp, vp]
+    lib.taper_step_latency_probe.argtypes = [vp, vp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                             ci, ci, vp, ctypes.POINTER(taper_probe_result)]
+    lib.taper_kernel_times.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.taper_strerror.argtypes = [ci]
+    lib.taper_strerror.restype = ctypes.c_char_p
+    lib.taper_last_error.restype = ctypes.c_char_p
+    for name in EXPORTED:
+        getattr(lib, name)
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != TAPER_OK:
+        lib = load_library()
+        msg = lib.taper_last_error().decode() or lib.taper_strerror(status).decode()
+        raise TaperError(status, msg)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(t) -> int:
+    """Device pointer of a torch tensor, or a raw int."""
+    return int(t) if isinstance(t, int) else int(t.data_ptr())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    return int(stream) if isinstance(stream, int) else int(stream.cuda_stream)
+
+
+class Plan:
+    """One decode step's integer metadata (taper_plan)."""
+
+    def __init__(self, ctx: "Context", handle: int):
+        self.ctx, self._h = ctx, handle
+
+    def free(self):
+        if self._h:
+            load_library().taper_plan_free(self._h)
+            self._h = 0
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+    def export(self) -> dict:
+        """taper_plan_export, copied into numpy arrays."""
+        v = taper_plan_view()
+        _check(load_library().taper_plan_export(self._h, ctypes.byref(v)))
+        S, G = v.n_seqs, v.n_groups
+        n_parts = v.n_parts_shared + v.n_parts_private
+        arr = lambda p, n: np.ctypeslib.as_array(p, shape=(n,)).copy() if n else np.zeros(0, np.int32)
+        items = np.ctypeslib.as_array(ctypes.cast(v.items, _I32P), shape=(v.n_items, 8)).copy()
+        n_merge = int(arr(v.merge_start, S + 1)[-1])
+        merge = np.ctypeslib.as_array(ctypes.cast(v.merge, _I32P), shape=(n_merge, 2)).copy()
+        return dict(n_seqs=S, n_groups=G, ctx_len=arr(v.ctx_len, S), n_prefix_pages=arr(v.n_prefix_pages, S),
+                    n_suffix_pages=arr(v.n_suffix_pages, S), group_start=arr(v.group_start, G + 1),
+                    items=items, item_fields=[f[0] for f in taper_work_item._fields_],
+                    n_parts_shared=v.n_parts_shared, n_parts_private=v.n_parts_private,
+                    part_start=arr(v.part_start, n_parts + 1), merge_start=arr(v.merge_start, S + 1), merge=merge,
+                    n_partial_rows=int(v.n_partial_rows), tokens_unique=int(v.tokens_unique),
+                    tokens_logical=int(v.tokens_logical))
+
+    def resolve_slots_host(self, stride: int) -> np.ndarray:
+        S = self.export()["n_seqs"]
+        out = np.zeros((S, stride), np.int64)
+        _check(load_library().taper_plan_resolve_slots_host(self._h, out.ctypes.data, stride))
+        return out
+
+    def resolve_slots(self, slots_dev, stride: int, stream=None):
+        _check(load_library().taper_plan_resolve_slots(self.ctx._h, self._h, _ptr(slots_dev), stride, _stream(stream)))
+
+
+class Context:
+    """taper_ctx: shape + workspace.  device=-1 gives a host-only context."""
+
+    def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, page_size: int = 16,
+                 scale: Optional[float] = None, device: int = 0):
+        lib = load_library()
+        cfg = taper_attn_config(n_q_heads, n_kv_heads, head_dim, page_size,
+                                float(scale if scale is not None else head_dim ** -0.5), device)
+        h = ctypes.c_void_p()
+        _check(lib.taper_create(ctypes.byref(cfg), ctypes.byref(h)))
+        self._h = h.value
+        self.cfg = cfg
+
+    def close(self):
+        if self._h:
+            load_library().taper_destroy(self._h)
+            self._h = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def plan_build(self, block_table, branch_group, prefix_len, suffix_len, n_pool_pages: int,
+                   target_workgroups: int = 0, share_prefix: bool = True, max_branches_per_item: int = 0,
+                   stream=None) -> Plan:
+        bt = _i32(block_table)
+        grp, pl, sl = _i32(branch_group), _i32(prefix_len), _i32(suffix_len)
+        if bt.ndim != 2 or not (len(grp) == len(pl) == len(sl) == bt.shape[0]):
+            raise TaperError(TAPER_EINVAL, "block_table must be [S, max_blocks] and the per-sequence arrays length S")
+        opts = taper_plan_options(target_workgroups, int(share_prefix), max_branches_per_item, 0)
+        h = ctypes.c_void_p()
+        st = 0 if self.cfg.device < 0 else _stream(stream)
+        _check(load_library().taper_plan_build(self._h, bt.shape[0], bt.ctypes.data, bt.shape[1], grp.ctypes.data,
+                                               pl.ctypes.data, sl.ctypes.data, int(n_pool_pages), ctypes.byref(opts),
+                                               st, ctypes.byref(h)))
+        return Plan(self, h.value)
+
+    def decode_step_attention(self, plan: Plan, q, kv_pages, out, lse=None, stream=None):
+        _check(load_library().taper_decode_step_attention(self._h, plan._h, _ptr(q), _ptr(kv_pages), _ptr(out),
+                                                          _ptr(lse) if lse is not None else None, _stream(stream)))
+
+    def decode_step_attention_simple(self, q, kv_pages, n_pool_pages, block_table, branch_group, prefix_len,
+                                     suffix_len, out, stream=None):
+        bt = _i32(block_table)
+        grp, pl, sl = _i32(branch_group), _i32(prefix_len), _i32(suffix_len)
+        _check(load_library().taper_decode_step_attention_simple(
+            self._h, bt.shape[0], _ptr(q), _ptr(kv_pages), int(n_pool_pages), bt.ctypes.data, bt.shape[1],
+            grp.ctypes.data, pl.ctypes.data, sl.ctypes.data, _ptr(out), _stream(stream)))
+
+    def step_latency_probe(self, plan: Plan, q_layers: Sequence, kv_layers: Sequence, out_layers: Sequence,
+                           warmup: int = 10, iters: int = 50, stream=None) -> taper_probe_result:
+        n = len(q_layers)
+        assert len(kv_layers) == n and len(out_layers) == n
+        mk = lambda ts: (ctypes.c_void_p * n)(*[_ptr(t) for t in ts])
+        res = taper_probe_result()
+        _check(load_library().taper_step_latency_probe(self._h, plan._h, n, mk(q_layers), mk(kv_layers),
+                                                       mk(out_layers), warmup, iters, _stream(stream),
+                                                       ctypes.byref(res)))
+        return res
+
+    def kernel_times(self, plan: Plan, q, kv_pages, out, warmup: int = 5, iters: int = 20, stream=None):
+        us = (ctypes.c_double * 3)()
+        _check(load_library().taper_kernel_times(self._h, plan._h, _ptr(q), _ptr(kv_pages), _ptr(out), warmup, iters,
+                                                 _stream(stream), us))
+        return dict(shared_us=us[0], private_us=us[1], merge_us=us[2])

@@ -1,0 +1,432 @@
+// C-ABI layer: context / plan lifetime, device copies of the plan, launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "taper_attn.h"
+#include "taper_internal.h"
+#include "taper_plan.h"
+
+namespace {
+thread_local std::string g_last_error;
+
+int fail(int code, const std::string& msg) {
+    g_last_error = msg;
+    return code;
+}
+int fail_hip(hipError_t e, const char* what) {
+    g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+    return TAPER_EHIP;
+}
+#define HIP_TRY(expr)                                  \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return fail_hip(e_, #expr); \
+    } while (0)
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+}  // namespace
+
+struct taper_ctx {
+    taper_attn_config cfg;
+    bool host_only = false;
+    void* ws = nullptr;  // partials workspace: [rows] float2 (m, l) then [rows][D] float
+    int64_t ws_rows = 0;
+};
+
+struct taper_plan {
+    taper_ctx* ctx = nullptr;
+    taper::HostPlan host;
+    void* dev = nullptr;          // one device allocation holding every integer array
+    void* staging = nullptr;      // pinned host image of `dev`
+    size_t dev_bytes = 0;
+    hipEvent_t uploaded = nullptr;
+    // device pointers into `dev`
+    const int32_t* d_bt = nullptr;
+    const taper_work_item* d_items = nullptr;
+    const int32_t* d_part_start = nullptr;
+    const int32_t* d_merge_start = nullptr;
+    const taper_merge_entry* d_merge = nullptr;
+    const int32_t* d_prefix_len = nullptr;
+    const int32_t* d_n_prefix_pages = nullptr;
+    const int32_t* d_ctx_len = nullptr;
+};
+
+namespace {
+
+int ensure_workspace(taper_ctx* ctx, int64_t rows) {
+    if (rows <= ctx->ws_rows) return TAPER_OK;
+    if (ctx->ws) {
+        HIP_TRY(hipDeviceSynchronize());
+        HIP_TRY(hipFree(ctx->ws));
+        ctx->ws = nullptr;
+        ctx->ws_rows = 0;
+    }
+    const int64_t want = rows + rows / 4 + 1024;  // head-room so steady-state steps do not reallocate
+    const size_t bytes = align_up((size_t)want * sizeof(float2), 256) + (size_t)want * ctx->cfg.head_dim * sizeof(float);
+    hipError_t e = hipMalloc(&ctx->ws, bytes);
+    if (e != hipSuccess) {
+        ctx->ws = nullptr;
+        g_last_error = std::string("workspace hipMalloc: ") + hipGetErrorString(e);
+        return TAPER_ENOMEM;
+    }
+    ctx->ws_rows = want;
+    return TAPER_OK;
+}
+
+taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const void* q, const void* kv, void* out,
+                          float* lse) {
+    taper::StepArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.q = q;
+    a.kv = kv;
+    a.out = out;
+    a.lse = lse;
+    a.bt = plan->d_bt;
+    a.items = plan->d_items;
+    a.part_start = plan->d_part_start;
+    a.merge_start = plan->d_merge_start;
+    a.merge = plan->d_merge;
+    a.prefix_len = plan->d_prefix_len;
+    a.n_prefix_pages = plan->d_n_prefix_pages;
+    a.ctx_len = plan->d_ctx_len;
+    a.ws_ml = (float2*)ctx->ws;
+    a.ws_o = (float*)((char*)ctx->ws + align_up((size_t)ctx->ws_rows * sizeof(float2), 256));
+    a.bt_stride = plan->host.bt_stride;
+    a.n_seqs = plan->host.n_seqs;
+    a.n_q_heads = ctx->cfg.n_q_heads;
+    a.n_kv_heads = ctx->cfg.n_kv_heads;
+    a.gqa = ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads;
+    a.head_dim = ctx->cfg.head_dim;
+    a.n_parts_shared = plan->host.n_parts_shared;
+    a.n_parts_private = plan->host.n_parts_private;
+    a.max_row_tiles_shared = plan->host.max_row_tiles_shared;
+    a.scale_log2e = ctx->cfg.scale * 1.4426950408889634f;
+    return a;
+}
+
+int check_step(const taper_ctx* ctx, const taper_plan* plan) {
+    if (!ctx || !plan) return fail(TAPER_EINVAL, "null ctx or plan");
+    if (plan->ctx != ctx) return fail(TAPER_EINVAL, "plan was built on another context");
+    if (ctx->host_only || !plan->dev) return fail(TAPER_EHIP, "host-only context: no device work possible");
+    if (plan->host.n_partial_rows > ctx->ws_rows) return fail(TAPER_EINVAL, "workspace smaller than the plan needs");
+    return TAPER_OK;
+}
+
+int enqueue_step(const taper::StepArgs& a, hipStream_t s) {
+    HIP_TRY(taper::launch_shared(a, s));
+    HIP_TRY(taper::launch_private(a, s));
+    HIP_TRY(taper::launch_merge(a, s));
+    return TAPER_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* taper_strerror(int status) {
+    switch (status) {
+        case TAPER_OK: return "ok";
+        case TAPER_EINVAL: return "invalid argument";
+        case TAPER_EBLOCK: return "block-table entry outside the pool";
+        case TAPER_EGROUP: return "malformed request grouping";
+        case TAPER_ELEN: return "bad sequence length";
+        case TAPER_EHIP: return "HIP runtime error";
+        case TAPER_ENOMEM: return "out of memory";
+        default: return "unknown status";
+    }
+}
+
+const char* taper_last_error(void) { return g_last_error.c_str(); }
+
+int taper_create(const taper_attn_config* cfg, taper_ctx** out_ctx) {
+    if (!cfg || !out_ctx) return fail(TAPER_EINVAL, "null argument");
+    std::string err;
+    int st = taper::validate_config(*cfg, &err);
+    if (st != TAPER_OK) return fail(st, err);
+    taper_ctx* ctx = new (std::nothrow) taper_ctx();
+    if (!ctx) return fail(TAPER_ENOMEM, "host allocation failed");
+    ctx->cfg = *cfg;
+    ctx->host_only = cfg->device < 0;
+    if (!ctx->host_only) {
+        int n = 0;
+        hipError_t e = hipGetDeviceCount(&n);
+        if (e != hipSuccess || cfg->device >= n) {
+            delete ctx;
+            return fail(TAPER_EHIP, "no such HIP device");
+        }
+        e = hipSetDevice(cfg->device);
+        if (e != hipSuccess) {
+            delete ctx;
+            return fail_hip(e, "hipSetDevice");
+        }
+    }
+    *out_ctx = ctx;
+    return TAPER_OK;
+}
+
+void taper_destroy(taper_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->ws) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(ctx->ws);
+    }
+    delete ctx;
+}
+
+int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int bt_row_stride,
+                     const int32_t* branch_group, const int32_t* prefix_len, const int32_t* suffix_len,
+                     int64_t n_pool_pages, const taper_plan_options* opts, void* hip_stream, taper_plan** out_plan) {
+    if (!ctx || !out_plan) return fail(TAPER_EINVAL, "null argument");
+    taper_plan* plan = new (std::nothrow) taper_plan();
+    if (!plan) return fail(TAPER_ENOMEM, "host allocation failed");
+    plan->ctx = ctx;
+    std::string err;
+    int st = taper::build_host_plan(ctx->cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len,
+                                    suffix_len, n_pool_pages, opts, &plan->host, &err);
+    if (st != TAPER_OK) {
+        delete plan;
+        return fail(st, err);
+    }
+    if (ctx->host_only) {
+        *out_plan = plan;
+        return TAPER_OK;
+    }
+    const taper::HostPlan& h = plan->host;
+    // one image: bt | items | part_start | merge_start | merge | prefix_len | n_prefix_pages | ctx_len
+    struct Piece {
+        const void* src;
+        size_t bytes;
+        size_t off;
+    };
+    std::vector<Piece> pieces = {
+        {h.block_table.data(), h.block_table.size() * sizeof(int32_t), 0},
+        {h.items.data(), h.items.size() * sizeof(taper_work_item), 0},
+        {h.part_start.data(), h.part_start.size() * sizeof(int32_t), 0},
+        {h.merge_start.data(), h.merge_start.size() * sizeof(int32_t), 0},
+        {h.merge.data(), h.merge.size() * sizeof(taper_merge_entry), 0},
+        {h.prefix_len.data(), h.prefix_len.size() * sizeof(int32_t), 0},
+        {h.n_prefix_pages.data(), h.n_prefix_pages.size() * sizeof(int32_t), 0},
+        {h.ctx_len.data(), h.ctx_len.size() * sizeof(int32_t), 0},
+    };
+    size_t total = 0;
+    for (Piece& p : pieces) {
+        p.off = total;
+        total += align_up(std::max<size_t>(p.bytes, 16), 256);
+    }
+    plan->dev_bytes = total;
+    hipError_t e = hipSetDevice(ctx->cfg.device);
+    if (e == hipSuccess) e = hipHostMalloc(&plan->staging, total, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMalloc(&plan->dev, total);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&plan->uploaded, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        std::string msg = std::string("plan allocation: ") + hipGetErrorString(e);
+        taper_plan_free(plan);
+        return fail(TAPER_ENOMEM, msg);
+    }
+    for (const Piece& p : pieces) std::memcpy((char*)plan->staging + p.off, p.src, p.bytes);
+    hipStream_t s = (hipStream_t)hip_stream;
+    e = hipMemcpyAsync(plan->dev, plan->staging, total, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipEventRecord(plan->uploaded, s);
+    if (e != hipSuccess) {
+        std::string msg = std::string("plan upload: ") + hipGetErrorString(e);
+        taper_plan_free(plan);
+        return fail(TAPER_EHIP, msg);
+    }
+    char* d = (char*)plan->dev;
+    plan->d_bt = (const int32_t*)(d + pieces[0].off);
+    plan->d_items = (const taper_work_item*)(d + pieces[1].off);
+    plan->d_part_start = (const int32_t*)(d + pieces[2].off);
+    plan->d_merge_start = (const int32_t*)(d + pieces[3].off);
+    plan->d_merge = (const taper_merge_entry*)(d + pieces[4].off);
+    plan->d_prefix_len = (const int32_t*)(d + pieces[5].off);
+    plan->d_n_prefix_pages = (const int32_t*)(d + pieces[6].off);
+    plan->d_ctx_len = (const int32_t*)(d + pieces[7].off);
+    st = ensure_workspace(ctx, h.n_partial_rows);
+    if (st != TAPER_OK) {
+        std::string keep = g_last_error;
+        taper_plan_free(plan);
+        return fail(st, keep);
+    }
+    *out_plan = plan;
+    return TAPER_OK;
+}
+
+void taper_plan_free(taper_plan* plan) {
+    if (!plan) return;
+    if (plan->uploaded) {
+        (void)hipEventSynchronize(plan->uploaded);  // the pinned image must outlive the copy
+        (void)hipEventDestroy(plan->uploaded);
+    }
+    if (plan->dev) (void)hipFree(plan->dev);  // hipFree waits for work that may still read it
+    if (plan->staging) (void)hipHostFree(plan->staging);
+    delete plan;
+}
+
+int taper_plan_export(const taper_plan* plan, taper_plan_view* v) {
+    if (!plan || !v) return fail(TAPER_EINVAL, "null argument");
+    const taper::HostPlan& h = plan->host;
+    std::memset(v, 0, sizeof *v);
+    v->n_seqs = h.n_seqs;
+    v->n_groups = h.n_groups;
+    v->ctx_len = h.ctx_len.data();
+    v->n_prefix_pages = h.n_prefix_pages.data();
+    v->n_suffix_pages = h.n_suffix_pages.data();
+    v->group_start = h.group_start.data();
+    v->n_items = (int32_t)h.items.size();
+    v->items = h.items.data();
+    v->n_parts_shared = h.n_parts_shared;
+    v->n_parts_private = h.n_parts_private;
+    v->part_start = h.part_start.data();
+    v->merge_start = h.merge_start.data();
+    v->merge = h.merge.data();
+    v->n_partial_rows = h.n_partial_rows;
+    v->tokens_unique = h.tokens_unique;
+    v->tokens_logical = h.tokens_logical;
+    return TAPER_OK;
+}
+
+int taper_plan_resolve_slots_host(const taper_plan* plan, int64_t* slots, int64_t stride) {
+    if (!plan || !slots || stride < 0) return fail(TAPER_EINVAL, "bad argument");
+    taper::resolve_slots_host(plan->host, plan->ctx->cfg.page_size, slots, stride);
+    return TAPER_OK;
+}
+
+int taper_plan_resolve_slots(taper_ctx* ctx, const taper_plan* plan, int64_t* slots, int64_t stride,
+                             void* hip_stream) {
+    int st = check_step(ctx, plan);
+    if (st != TAPER_OK) return st;
+    if (!slots || stride < 0) return fail(TAPER_EINVAL, "bad argument");
+    taper::StepArgs a = make_args(ctx, plan, nullptr, nullptr, nullptr, nullptr);
+    HIP_TRY(taper::launch_resolve_slots(a, slots, stride, (hipStream_t)hip_stream));
+    return TAPER_OK;
+}
+
+int taper_decode_step_attention(taper_ctx* ctx, const taper_plan* plan, const void* q, const void* kv_pages,
+                                void* out, float* lse, void* hip_stream) {
+    int st = check_step(ctx, plan);
+    if (st != TAPER_OK) return st;
+    if (!q || !kv_pages || !out) return fail(TAPER_EINVAL, "null tensor pointer");
+    return enqueue_step(make_args(ctx, plan, q, kv_pages, out, lse), (hipStream_t)hip_stream);
+}
+
+int taper_decode_step_attention_simple(taper_ctx* ctx, int n_seqs, const void* q, const void* kv_pages,
+                                       int64_t n_pool_pages, const int32_t* block_table, int bt_row_stride,
+                                       const int32_t* branch_group, const int32_t* prefix_len,
+                                       const int32_t* suffix_len, void* out, void* hip_stream) {
+    taper_plan* plan = nullptr;
+    int st = taper_plan_build(ctx, n_seqs, block_table, bt_row_stride, branch_group, prefix_len, suffix_len,
+                              n_pool_pages, nullptr, hip_stream, &plan);
+    if (st != TAPER_OK) return st;
+    st = taper_decode_step_attention(ctx, plan, q, kv_pages, out, nullptr, hip_stream);
+    if (st == TAPER_OK) {
+        hipError_t e = hipStreamSynchronize((hipStream_t)hip_stream);
+        if (e != hipSuccess) st = fail_hip(e, "hipStreamSynchronize");
+    }
+    taper_plan_free(plan);
+    return st;
+}
+
+int taper_step_latency_probe(taper_ctx* ctx, const taper_plan* plan, int n_layers, const void* const* q_per_layer,
+                             const void* const* kv_per_layer, void* const* out_per_layer, int warmup, int iters,
+                             void* hip_stream, taper_probe_result* res) {
+    int st = check_step(ctx, plan);
+    if (st != TAPER_OK) return st;
+    if (n_layers < 1 || iters < 1 || warmup < 0 || !q_per_layer || !kv_per_layer || !out_per_layer || !res)
+        return fail(TAPER_EINVAL, "bad probe argument");
+    for (int l = 0; l < n_layers; ++l)
+        if (!q_per_layer[l] || !kv_per_layer[l] || !out_per_layer[l]) return fail(TAPER_EINVAL, "null layer pointer");
+    hipStream_t s = (hipStream_t)hip_stream;
+    std::vector<hipEvent_t> ev(2 * (size_t)iters, nullptr);
+    for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
+    int rc = TAPER_OK;
+    for (int i = 0; i < warmup + iters && rc == TAPER_OK; ++i) {
+        const int k = i - warmup;
+        if (k >= 0 && hipEventRecord(ev[2 * k], s) != hipSuccess) rc = fail(TAPER_EHIP, "hipEventRecord");
+        for (int l = 0; l < n_layers && rc == TAPER_OK; ++l)
+            rc = enqueue_step(make_args(ctx, plan, q_per_layer[l], kv_per_layer[l], out_per_layer[l], nullptr), s);
+        if (k >= 0 && rc == TAPER_OK && hipEventRecord(ev[2 * k + 1], s) != hipSuccess)
+            rc = fail(TAPER_EHIP, "hipEventRecord");
+    }
+    hipError_t es = hipStreamSynchronize(s);
+    if (rc == TAPER_OK && es != hipSuccess) rc = fail_hip(es, "hipStreamSynchronize");
+    std::vector<double> us;
+    if (rc == TAPER_OK) {
+        for (int k = 0; k < iters; ++k) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, ev[2 * k], ev[2 * k + 1]) != hipSuccess) {
+                rc = fail(TAPER_EHIP, "hipEventElapsedTime");
+                break;
+            }
+            us.push_back(ms * 1000.0);
+        }
+    }
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    if (rc != TAPER_OK) return rc;
+    std::sort(us.begin(), us.end());
+    double sum = 0;
+    for (double u : us) sum += u;
+    std::memset(res, 0, sizeof *res);
+    res->us_min = us.front();
+    res->us_median = (us.size() % 2) ? us[us.size() / 2] : 0.5 * (us[us.size() / 2 - 1] + us[us.size() / 2]);
+    res->us_mean = sum / us.size();
+    res->n_tokens = plan->host.n_seqs;
+    res->n_layers = n_layers;
+    res->l_context = plan->host.tokens_logical;
+    const int64_t bpt = 2LL * ctx->cfg.n_kv_heads * ctx->cfg.head_dim * 2;
+    res->kv_bytes_unique = plan->host.tokens_unique * bpt;
+    res->kv_bytes_logical = plan->host.tokens_logical * bpt;
+    res->gbps_unique = (double)res->kv_bytes_unique * n_layers / (res->us_median * 1e-6) / 1e9;
+    res->gbps_logical = (double)res->kv_bytes_logical * n_layers / (res->us_median * 1e-6) / 1e9;
+    return TAPER_OK;
+}
+
+int taper_kernel_times(taper_ctx* ctx, const taper_plan* plan, const void* q, const void* kv_pages, void* out,
+                       int warmup, int iters, void* hip_stream, double us[3]) {
+    int st = check_step(ctx, plan);
+    if (st != TAPER_OK) return st;
+    if (!q || !kv_pages || !out || !us || iters < 1 || warmup < 0) return fail(TAPER_EINVAL, "bad argument");
+    hipStream_t s = (hipStream_t)hip_stream;
+    const taper::StepArgs a = make_args(ctx, plan, q, kv_pages, out, nullptr);
+    std::vector<hipEvent_t> ev(4 * (size_t)iters, nullptr);
+    for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
+    int rc = TAPER_OK;
+    for (int i = 0; i < warmup + iters && rc == TAPER_OK; ++i) {
+        const int k = i - warmup;
+        hipError_t e = hipSuccess;
+        if (k >= 0) e = hipEventRecord(ev[4 * k], s);
+        if (e == hipSuccess) e = taper::launch_shared(a, s);
+        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[4 * k + 1], s);
+        if (e == hipSuccess) e = taper::launch_private(a, s);
+        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[4 * k + 2], s);
+        if (e == hipSuccess) e = taper::launch_merge(a, s);
+        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[4 * k + 3], s);
+        if (e != hipSuccess) rc = fail_hip(e, "kernel timing enqueue");
+    }
+    hipError_t es = hipStreamSynchronize(s);
+    if (rc == TAPER_OK && es != hipSuccess) rc = fail_hip(es, "hipStreamSynchronize");
+    double acc[3] = {0, 0, 0};
+    if (rc == TAPER_OK) {
+        for (int k = 0; k < iters && rc == TAPER_OK; ++k)
+            for (int j = 0; j < 3; ++j) {
+                float ms = 0.f;
+                if (hipEventElapsedTime(&ms, ev[4 * k + j], ev[4 * k + j + 1]) != hipSuccess) {
+                    rc = fail(TAPER_EHIP, "hipEventElapsedTime");
+                    break;
+                }
+                acc[j] += ms * 1000.0;
+            }
+    }
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    if (rc != TAPER_OK) return rc;
+    for (int j = 0; j < 3; ++j) us[j] = acc[j] / iters;
+    return TAPER_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,40 @@
+// Interface between the C-ABI layer and the HIP kernels (device pointers only).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "taper_attn.h"
+
+namespace taper {
+
+// Device-resident integer metadata of one step plus the tensors of one layer.
+struct StepArgs {
+    const void* q;             // bf16 [S][Hq][D]
+    const void* kv;            // bf16 pool
+    void* out;                 // bf16 [S][Hq][D]
+    float* lse;                // f32 [S][Hq] or null
+    const int32_t* bt;         // [S][bt_stride]
+    const taper_work_item* items;
+    const int32_t* part_start;
+    const int32_t* merge_start;
+    const taper_merge_entry* merge;
+    const int32_t* prefix_len;
+    const int32_t* n_prefix_pages;
+    const int32_t* ctx_len;
+    float2* ws_ml;             // [n_partial_rows] (running max in log2 units, sum)
+    float* ws_o;               // [n_partial_rows][D] unnormalised
+    int32_t bt_stride;
+    int32_t n_seqs;
+    int32_t n_q_heads, n_kv_heads, gqa, head_dim;
+    int32_t n_parts_shared, n_parts_private;
+    int32_t max_row_tiles_shared;
+    float scale_log2e;         // scale * log2(e)
+};
+
+hipError_t launch_shared(const StepArgs& a, hipStream_t s);
+hipError_t launch_private(const StepArgs& a, hipStream_t s);
+hipError_t launch_merge(const StepArgs& a, hipStream_t s);
+hipError_t launch_resolve_slots(const StepArgs& a, int64_t* slots, int64_t stride, hipStream_t s);
+
+}  // namespace taper

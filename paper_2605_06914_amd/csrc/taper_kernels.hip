@@ -1,0 +1,458 @@
+// gfx950 kernels for decode-step attention over a paged KV cache with shared
+// prefixes (paper §3.1: a branch attends to shared prefix ++ own tokens; all
+// branches of a request are served from one set of prefix pages).
+//
+// Everything is computed in "transposed" form so that no operand ever has to be
+// shuffled between lanes.  With 16x16x32 bf16 MFMA (A: 16 x 32, B: 32 x 16,
+// C: 16 x 16; lane l supplies A[l%16][8*(l/16)..+7], B[8*(l/16)..+7][l%16] and
+// receives C[4*(l/16)..+3][l%16]):
+//   S^T (tokens x rows) = K (tokens x d) * Q^T (d x rows)      A = K tile, B = Q^T
+//   O^T (d x rows)      = V^T (d x tokens) * P^T (tokens x rows) A = V^T,   B = P^T
+// The C fragment of S^T (lane: query row l%16, tokens 4*(l/16)..+3) is, after
+// exp and rounding, already the B fragment of P^T: the 32 tokens of an MFMA
+// k-step are two pages, lane group l/16 holding tokens 4*(l/16)..+3 of each.  The
+// pool layout (K in groups of 8 dims, V^T in groups of 4 tokens) makes the A
+// fragments contiguous 16-byte / 8-byte pieces with unit stride across lanes.
+//
+// Softmax state per query row (one lane column): running max m in log2 units
+// (scale*log2(e) folded in), running sum l, unnormalised O.  Partials of the KV
+// chunks of a sequence are combined by merge_kernel through their (m, l).
+#include "taper_internal.h"
+
+namespace taper {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+
+#define DEV __device__ __forceinline__
+
+DEV f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+DEV bf16x8 cat(bf16x4 a, bf16x4 b) { return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7); }
+DEV float max4(f32x4 v) { return fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])); }
+
+// Scores of invalid tokens of a chunk's last 32-token block -> -inf.
+// sx: tokens 4*qd+i of the block's first page, sy: of its second page.
+DEV void mask_tail(f32x4& sx, f32x4& sy, int qd, int n_valid) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (4 * qd + i >= n_valid) sx[i] = -INFINITY;
+        if (16 + 4 * qd + i >= n_valid) sy[i] = -INFINITY;
+    }
+}
+
+// Online softmax over one 32-token block for one 16-row tile.  Every block passed
+// in holds at least one valid token, so the new max is finite.
+template <int DT>
+DEV bf16x8 softmax_block(f32x4 sx, f32x4 sy, float c, float& m, float& l, f32x4 (&O)[DT]) {
+    float mx = fmaxf(max4(sx), max4(sy));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float mn = fmaxf(m, mx * c);
+    if (__any(mn > m)) {  // wave-uniform: rescale only when some row's max moved
+        const float alpha = fast_exp2(m - mn);
+        l *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) O[dt] *= alpha;
+        m = mn;
+    }
+    f32x8 p;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        p[i] = fast_exp2(fmaf(sx[i], c, -m));
+        p[4 + i] = fast_exp2(fmaf(sy[i], c, -m));
+    }
+    l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+    return __builtin_convertvector(p, bf16x8);
+}
+
+DEV float sum_lane_groups(float v) {
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+// ---------------------------------------------------------------------------
+// Private / serial kernel: one sequence's g query rows (one 16-row tile, rows
+// >= g idle) against a chunk of that sequence's own pages.  No reuse across
+// waves, so K/V go straight from HBM into MFMA operand registers; the four
+// waves of a workgroup take alternate 32-token blocks and combine through LDS.
+// ---------------------------------------------------------------------------
+template <int D>
+struct KVRegs {
+    bf16x8 kx[D / 32], ky[D / 32];
+    bf16x4 va[D / 16], vb[D / 16];
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void private_kernel(StepArgs a) {
+    constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D, OST = D + 4;
+    __shared__ __attribute__((aligned(16))) float sm_o[4][16][OST];
+    __shared__ float2 sm_ml[4][16];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, qd = lane >> 4;
+    const int Hkv = a.n_kv_heads, g = a.gqa;
+    const int part = a.n_parts_shared + blockIdx.x / Hkv;
+    const int hk = blockIdx.x % Hkv;
+    const __bf16* __restrict__ kvb = (const __bf16*)a.kv;
+    const int64_t page_elems = 2LL * Hkv * TILE;
+    const float c = a.scale_log2e;
+    const int koff = lane * 8, voff = qd * (4 * D) + n * 4;
+
+    const int it0 = a.part_start[part], it1 = a.part_start[part + 1];
+    for (int it = it0; it < it1; ++it) {
+        const taper_work_item item = a.items[it];
+        const int32_t* __restrict__ row = a.bt + (int64_t)item.seq0 * a.bt_stride + item.page0;
+        const int n_tok = item.n_tokens;
+        const int n_pages = (n_tok + 15) >> 4;
+        const int n_blocks = (n_tok + 31) >> 5;
+
+        bf16x8 qf[KS];
+        {
+            const __bf16* qrow = (const __bf16*)a.q + ((int64_t)item.seq0 * a.n_q_heads + hk * g + (n < g ? n : 0)) * D;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                bf16x8 v = *(const bf16x8*)(qrow + 8 * (4 * j + qd));
+                if (n >= g) v = (bf16x8)(0);
+                qf[j] = v;
+            }
+        }
+        float m = -INFINITY, l = 0.f;
+        f32x4 O[DT];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) O[dt] = (f32x4)(0.f);
+
+        auto load_block = [&](int b, KVRegs<D>& r) {
+            const int ia = 2 * b, ib = (2 * b + 1 < n_pages) ? 2 * b + 1 : ia;
+            const int64_t pa = row[ia], pb = row[ib];
+            const __bf16* ka = kvb + pa * page_elems + (int64_t)hk * TILE;
+            const __bf16* kb = kvb + pb * page_elems + (int64_t)hk * TILE;
+            const __bf16* va = ka + (int64_t)Hkv * TILE;
+            const __bf16* vb = kb + (int64_t)Hkv * TILE;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                r.kx[j] = *(const bf16x8*)(ka + koff + j * 512);
+                r.ky[j] = *(const bf16x8*)(kb + koff + j * 512);
+            }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                r.va[dt] = *(const bf16x4*)(va + voff + dt * 64);
+                r.vb[dt] = *(const bf16x4*)(vb + voff + dt * 64);
+            }
+        };
+        auto compute_block = [&](int b, const KVRegs<D>& r) {
+            f32x4 sx = (f32x4)(0.f), sy = (f32x4)(0.f);
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                sx = mfma16(r.kx[j], qf[j], sx);
+                sy = mfma16(r.ky[j], qf[j], sy);
+            }
+            const int nv = n_tok - 32 * b;
+            if (nv < 32) mask_tail(sx, sy, qd, nv);
+            const bf16x8 pf = softmax_block<DT>(sx, sy, c, m, l, O);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) O[dt] = mfma16(cat(r.va[dt], r.vb[dt]), pf, O[dt]);
+        };
+
+        KVRegs<D> r0, r1;
+        int b = wave;
+        if (b < n_blocks) load_block(b, r0);
+        while (b < n_blocks) {
+            const int b1 = b + 4;
+            if (b1 < n_blocks) load_block(b1, r1);
+            compute_block(b, r0);
+            if (b1 >= n_blocks) break;
+            const int b2 = b1 + 4;
+            if (b2 < n_blocks) load_block(b2, r0);
+            compute_block(b1, r1);
+            b = b2;
+        }
+
+        // combine the four waves' states
+        l = sum_lane_groups(l);
+        if (n < g) {
+            if (qd == 0) sm_ml[wave][n] = make_float2(m, l);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) *(f32x4*)&sm_o[wave][n][16 * dt + 4 * qd] = O[dt];
+        }
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < g * (D / 4); idx += 256) {
+            const int r = idx / (D / 4), d4 = idx % (D / 4);
+            float mw[4], M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                mw[w] = sm_ml[w][r].x;
+                M = fmaxf(M, mw[w]);
+            }
+            float L = 0.f;
+            f32x4 acc = (f32x4)(0.f);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float wg = fast_exp2(mw[w] - M);
+                L += wg * sm_ml[w][r].y;
+                acc += wg * *(const f32x4*)&sm_o[w][r][4 * d4];
+            }
+            const int64_t slot = (int64_t)item.part_base + hk * g + r;
+            *(f32x4*)(a.ws_o + slot * D + 4 * d4) = acc;
+            if (d4 == 0) a.ws_ml[slot] = make_float2(M, L);
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Shared-prefix kernel: a chunk of one request's prefix pages is staged in LDS
+// once (64 tokens per iteration, double buffered) and multiplied against the
+// query rows of all n_branch admitted branches x g heads.  16-row tiles are
+// dealt round-robin to the four waves, up to NTW tiles per wave.
+// ---------------------------------------------------------------------------
+template <int D, int NTW>
+__global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void shared_kernel(StepArgs a) {
+    constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D;
+    constexpr int QE = 4 * D;             // elements of one 4-token quarter of a V tile
+    constexpr int VQ = QE + 64;           // padded quarter: odd multiple of 128 B -> quarters alternate bank halves
+    constexpr int PAGE_LDS = TILE + 4 * VQ;
+    constexpr int BUF = 4 * PAGE_LDS;     // 4 pages = 64 tokens
+    __shared__ __attribute__((aligned(16))) __bf16 lds[2 * BUF];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, qd = lane >> 4;
+    const int Hkv = a.n_kv_heads, g = a.gqa;
+    const int part = blockIdx.x / Hkv;
+    const int hk = blockIdx.x % Hkv;
+    const __bf16* __restrict__ kvb = (const __bf16*)a.kv;
+    const int64_t page_elems = 2LL * Hkv * TILE;
+    const float c = a.scale_log2e;
+    const int se = tid * 8;                       // staging: this thread's element offset inside a tile
+    const bool stager = se < TILE;
+    const int sv = (se / QE) * VQ + se % QE;      // ... and inside the padded V tile in LDS
+    const int koff = lane * 8;
+    const int voff = TILE + qd * VQ + n * 4;
+
+    const int it0 = a.part_start[part], it1 = a.part_start[part + 1];
+    for (int it = it0; it < it1; ++it) {
+        const taper_work_item item = a.items[it];
+        const int32_t* __restrict__ row = a.bt + (int64_t)item.seq0 * a.bt_stride + item.page0;
+        const int n_tok = item.n_tokens;
+        const int n_pages = (n_tok + 15) >> 4;
+        const int n_blocks = (n_tok + 63) >> 6;
+        const int R = item.n_branch * g;           // query rows
+        const int tiles = (R + 15) >> 4;
+        int n_act = (tiles - wave + 3) >> 2;       // tiles wave, wave+4, ...
+        n_act = n_act < 0 ? 0 : (n_act > NTW ? NTW : n_act);
+
+        bf16x8 qf[NTW][KS];
+        float m[NTW], l[NTW];
+        f32x4 O[NTW][DT];
+#pragma unroll
+        for (int k = 0; k < NTW; ++k) {
+            const int r = 16 * (wave + 4 * k) + n;
+            const bool ok = k < n_act && r < R;
+            const int rr = ok ? r : 0;
+            const __bf16* qrow = (const __bf16*)a.q + ((int64_t)(item.seq0 + rr / g) * a.n_q_heads + hk * g + rr % g) * D;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                bf16x8 v = *(const bf16x8*)(qrow + 8 * (4 * j + qd));
+                if (!ok) v = (bf16x8)(0);
+                qf[k][j] = v;
+            }
+            m[k] = -INFINITY;
+            l[k] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) O[k][dt] = (f32x4)(0.f);
+        }
+
+        bf16x8 stg[8];
+        auto stage_load = [&](int b) {
+            if (stager) {
+#pragma unroll
+                for (int pg = 0; pg < 4; ++pg) {
+                    const int ip = 4 * b + pg < n_pages ? 4 * b + pg : n_pages - 1;
+                    const int64_t pid = row[ip];
+                    const __bf16* kp = kvb + pid * page_elems + (int64_t)hk * TILE + se;
+                    stg[2 * pg] = *(const bf16x8*)kp;
+                    stg[2 * pg + 1] = *(const bf16x8*)(kp + (int64_t)Hkv * TILE);
+                }
+            }
+        };
+        auto stage_store = [&](int buf) {
+            if (stager) {
+                __bf16* base = lds + buf * BUF;
+#pragma unroll
+                for (int pg = 0; pg < 4; ++pg) {
+                    *(bf16x8*)(base + pg * PAGE_LDS + se) = stg[2 * pg];
+                    *(bf16x8*)(base + pg * PAGE_LDS + TILE + sv) = stg[2 * pg + 1];
+                }
+            }
+        };
+        auto compute = [&](int b, int buf) {
+            if (n_act == 0) return;
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const int nv = n_tok - (64 * b + 32 * hf);
+                if (nv <= 0) break;
+                const __bf16* pa = lds + buf * BUF + (2 * hf) * PAGE_LDS;
+                const __bf16* pb = pa + PAGE_LDS;
+                bf16x8 kx[KS], ky[KS];
+#pragma unroll
+                for (int j = 0; j < KS; ++j) {
+                    kx[j] = *(const bf16x8*)(pa + koff + j * 512);
+                    ky[j] = *(const bf16x8*)(pb + koff + j * 512);
+                }
+                bf16x8 pf[NTW];
+#pragma unroll
+                for (int k = 0; k < NTW; ++k) {
+                    if (k < n_act) {
+                        f32x4 sx = (f32x4)(0.f), sy = (f32x4)(0.f);
+#pragma unroll
+                        for (int j = 0; j < KS; ++j) {
+                            sx = mfma16(kx[j], qf[k][j], sx);
+                            sy = mfma16(ky[j], qf[k][j], sy);
+                        }
+                        if (nv < 32) mask_tail(sx, sy, qd, nv);
+                        pf[k] = softmax_block<DT>(sx, sy, c, m[k], l[k], O[k]);
+                    }
+                }
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const bf16x8 vf = cat(*(const bf16x4*)(pa + voff + dt * 64), *(const bf16x4*)(pb + voff + dt * 64));
+#pragma unroll
+                    for (int k = 0; k < NTW; ++k)
+                        if (k < n_act) O[k][dt] = mfma16(vf, pf[k], O[k][dt]);
+                }
+            }
+        };
+
+        stage_load(0);
+        stage_store(0);
+        __syncthreads();
+        for (int b = 0; b < n_blocks; ++b) {
+            const bool more = b + 1 < n_blocks;
+            if (more) stage_load(b + 1);
+            compute(b, b & 1);
+            if (more) stage_store((b + 1) & 1);
+            __syncthreads();
+        }
+
+#pragma unroll
+        for (int k = 0; k < NTW; ++k) {
+            if (k < n_act) {
+                const float lt = sum_lane_groups(l[k]);
+                const int r = 16 * (wave + 4 * k) + n;
+                if (r < R) {
+                    const int64_t slot = (int64_t)item.part_base + (int64_t)hk * R + r;
+                    if (qd == 0) a.ws_ml[slot] = make_float2(m[k], lt);
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) *(f32x4*)(a.ws_o + slot * D + 16 * dt + 4 * qd) = O[k][dt];
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Log-sum-exp merge of a sequence's partials (its request's prefix chunks and
+// its own private chunks), normalisation and rounding to bf16.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(StepArgs a) {
+    const int s = blockIdx.x;
+    const int idx = blockIdx.y * 256 + threadIdx.x;
+    if (idx >= a.n_q_heads * (D / 4)) return;
+    const int h = idx / (D / 4), d4 = idx % (D / 4);
+    const int hk = h / a.gqa, j = h % a.gqa;
+    const int e0 = a.merge_start[s], e1 = a.merge_start[s + 1];
+    float M = -INFINITY;
+    for (int e = e0; e < e1; ++e) {
+        const taper_merge_entry me = a.merge[e];
+        M = fmaxf(M, a.ws_ml[(int64_t)me.first_row + (int64_t)hk * me.rows_per_head + j].x);
+    }
+    float L = 0.f;
+    f32x4 acc = (f32x4)(0.f);
+    for (int e = e0; e < e1; ++e) {
+        const taper_merge_entry me = a.merge[e];
+        const int64_t rowi = (int64_t)me.first_row + (int64_t)hk * me.rows_per_head + j;
+        const float2 ml = a.ws_ml[rowi];
+        const float w = fast_exp2(ml.x - M);
+        L += w * ml.y;
+        acc += w * *(const f32x4*)(a.ws_o + rowi * D + 4 * d4);
+    }
+    const float inv = 1.0f / L;
+    acc *= inv;
+    const bf16x4 o = __builtin_convertvector(acc, bf16x4);
+    *(bf16x4*)((__bf16*)a.out + ((int64_t)s * a.n_q_heads + h) * D + 4 * d4) = o;
+    if (a.lse && d4 == 0) a.lse[(int64_t)s * a.n_q_heads + h] = (M + __log2f(L)) * 0.6931471805599453f;
+}
+
+// Physical slot of every logical position, from the device copy of the plan.
+__global__ __launch_bounds__(256) void resolve_slots_kernel(StepArgs a, int64_t* slots, int64_t stride) {
+    const int s = blockIdx.x;
+    const int64_t t = (int64_t)blockIdx.y * 256 + threadIdx.x;
+    if (t >= stride) return;
+    int64_t v = -1;
+    if (t < a.ctx_len[s]) {
+        const int32_t* row = a.bt + (int64_t)s * a.bt_stride;
+        const int pl = a.prefix_len[s];
+        if (t < pl) {
+            v = (int64_t)row[t >> 4] * 16 + (t & 15);
+        } else {
+            const int64_t jj = t - pl;
+            v = (int64_t)row[a.n_prefix_pages[s] + (jj >> 4)] * 16 + (jj & 15);
+        }
+    }
+    slots[(int64_t)s * stride + t] = v;
+}
+
+// ---------------------------------------------------------------------------
+hipError_t launch_shared(const StepArgs& a, hipStream_t s) {
+    if (a.n_parts_shared == 0) return hipSuccess;
+    const dim3 grid(a.n_parts_shared * a.n_kv_heads), block(256);
+    const int ntw = (a.max_row_tiles_shared + 3) / 4;
+    if (a.head_dim == 128) {
+        if (ntw <= 1) hipLaunchKernelGGL((shared_kernel<128, 1>), grid, block, 0, s, a);
+        else if (ntw == 2) hipLaunchKernelGGL((shared_kernel<128, 2>), grid, block, 0, s, a);
+        else if (ntw == 3) hipLaunchKernelGGL((shared_kernel<128, 3>), grid, block, 0, s, a);
+        else return hipErrorInvalidValue;
+    } else if (a.head_dim == 64) {
+        if (ntw <= 1) hipLaunchKernelGGL((shared_kernel<64, 1>), grid, block, 0, s, a);
+        else if (ntw == 2) hipLaunchKernelGGL((shared_kernel<64, 2>), grid, block, 0, s, a);
+        else if (ntw == 3) hipLaunchKernelGGL((shared_kernel<64, 3>), grid, block, 0, s, a);
+        else return hipErrorInvalidValue;
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_private(const StepArgs& a, hipStream_t s) {
+    if (a.n_parts_private == 0) return hipSuccess;
+    const dim3 grid(a.n_parts_private * a.n_kv_heads), block(256);
+    if (a.head_dim == 128) hipLaunchKernelGGL((private_kernel<128>), grid, block, 0, s, a);
+    else if (a.head_dim == 64) hipLaunchKernelGGL((private_kernel<64>), grid, block, 0, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_merge(const StepArgs& a, hipStream_t s) {
+    const int per_seq = a.n_q_heads * (a.head_dim / 4);
+    const dim3 grid(a.n_seqs, (per_seq + 255) / 256), block(256);
+    if (a.head_dim == 128) hipLaunchKernelGGL((merge_kernel<128>), grid, block, 0, s, a);
+    else if (a.head_dim == 64) hipLaunchKernelGGL((merge_kernel<64>), grid, block, 0, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_resolve_slots(const StepArgs& a, int64_t* slots, int64_t stride, hipStream_t s) {
+    if (stride <= 0) return hipSuccess;
+    const dim3 grid(a.n_seqs, (unsigned)((stride + 255) / 256)), block(256);
+    hipLaunchKernelGGL(resolve_slots_kernel, grid, block, 0, s, a, slots, stride);
+    return hipGetLastError();
+}
+
+}  // namespace taper

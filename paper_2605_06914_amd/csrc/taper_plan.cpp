@@ -1,0 +1,290 @@
+// Host-side index resolution for one decode step (see taper_plan.h).
+//
+// Which KV each query row reads follows the visibility rule (paper §3.1): the
+// request's shared prefix, then the sequence's own private tokens.  The shared
+// prefix of a request with several admitted branches becomes "shared" work
+// (read once, multiplied against all branches' query rows); everything else is
+// "private" work (one sequence's rows).
+#include "taper_plan.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+
+namespace taper {
+
+static std::string fmt(const char* f, long long a = 0, long long b = 0, long long c = 0) {
+    char buf[256];
+    std::snprintf(buf, sizeof buf, f, a, b, c);
+    return buf;
+}
+
+int validate_config(const taper_attn_config& cfg, std::string* err) {
+    if (cfg.n_q_heads < 1 || cfg.n_kv_heads < 1 || cfg.n_q_heads % cfg.n_kv_heads != 0) {
+        *err = "n_q_heads must be a positive multiple of n_kv_heads";
+        return TAPER_EINVAL;
+    }
+    int g = cfg.n_q_heads / cfg.n_kv_heads;
+    if (g > 16) {
+        *err = "at most 16 query heads per KV head are supported";
+        return TAPER_EINVAL;
+    }
+    if (cfg.head_dim != 64 && cfg.head_dim != 128) {
+        *err = "head_dim must be 64 or 128";
+        return TAPER_EINVAL;
+    }
+    if (cfg.page_size != 16) {
+        *err = "page_size must be 16";
+        return TAPER_EINVAL;
+    }
+    if (!(cfg.scale > 0.0f) || !(cfg.scale < 1e30f)) {
+        *err = "scale must be positive and finite";
+        return TAPER_EINVAL;
+    }
+    return TAPER_OK;
+}
+
+namespace {
+
+struct Segment {
+    int32_t seq0, n_branch, page0, n_tokens, kind;
+};
+
+// Cut `segs` into at most n_parts workgroup shares of about equal token count, at
+// multiples of `blk` tokens from each segment's start.  Appends items (tagged
+// with part ids starting at part_id0) and returns the number of shares used.
+int partition(const std::vector<Segment>& segs, int n_parts, int blk, int part_id0,
+              std::vector<taper_work_item>* items) {
+    int64_t total_blocks = 0;
+    for (const Segment& s : segs) total_blocks += (s.n_tokens + blk - 1) / blk;
+    if (total_blocks == 0) return 0;
+    n_parts = (int)std::max<int64_t>(1, std::min<int64_t>(n_parts, total_blocks));
+    const int64_t quota = (total_blocks + n_parts - 1) / n_parts;
+    const int64_t sliver = std::max<int64_t>(1, quota / 8);
+    int part = 0;
+    int64_t fill = 0;
+    for (const Segment& s : segs) {
+        int64_t remaining = (s.n_tokens + blk - 1) / blk, off = 0;
+        while (remaining > 0) {
+            int64_t room = quota - fill;
+            if (fill > 0 && room < sliver && room < remaining) {  // not worth a separate partial
+                ++part;
+                fill = 0;
+                continue;
+            }
+            int64_t take = std::min(remaining, std::max<int64_t>(room, 1));
+            if (remaining - take > 0 && remaining - take < sliver) take = remaining;
+            taper_work_item it;
+            std::memset(&it, 0, sizeof it);
+            it.seq0 = s.seq0;
+            it.n_branch = s.n_branch;
+            it.page0 = s.page0 + (int32_t)(off * blk / 16);
+            it.n_tokens = (int32_t)std::min<int64_t>(take * blk, s.n_tokens - off * blk);
+            it.kind = s.kind;
+            it.part = part_id0 + part;
+            items->push_back(it);
+            fill += take;
+            off += take;
+            remaining -= take;
+            if (fill >= quota) {
+                ++part;
+                fill = 0;
+            }
+        }
+    }
+    return fill > 0 ? part + 1 : part;
+}
+
+}  // namespace
+
+int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* block_table, int bt_row_stride,
+                    const int32_t* branch_group, const int32_t* prefix_len, const int32_t* suffix_len,
+                    int64_t n_pool_pages, const taper_plan_options* opts, HostPlan* out, std::string* err) {
+    int st = validate_config(cfg, err);
+    if (st != TAPER_OK) return st;
+    if (!block_table || !branch_group || !prefix_len || !suffix_len || !out) {
+        *err = "null argument";
+        return TAPER_EINVAL;
+    }
+    if (n_seqs < 1 || bt_row_stride < 1 || n_pool_pages < 1) {
+        *err = "n_seqs, bt_row_stride and n_pool_pages must be positive";
+        return TAPER_EINVAL;
+    }
+    if (n_pool_pages > (int64_t)1 << 31) {
+        *err = "n_pool_pages exceeds the int32 page id range";
+        return TAPER_EINVAL;
+    }
+    const int P = cfg.page_size;
+    const int g = cfg.n_q_heads / cfg.n_kv_heads;
+    int target_wgs = opts && opts->target_workgroups > 0 ? opts->target_workgroups : 512;
+    const bool share_prefix = opts ? opts->share_prefix != 0 : true;
+    int max_tiles = kMaxRowTilesPerItem;
+    int cap_branches = std::max(2, max_tiles * 16 / g);
+    if (opts && opts->max_branches_per_item > 0) cap_branches = std::max(1, std::min(cap_branches, opts->max_branches_per_item));
+
+    HostPlan& p = *out;
+    p = HostPlan();
+    p.n_seqs = n_seqs;
+    p.bt_stride = bt_row_stride;
+    p.n_pool_pages = n_pool_pages;
+    p.prefix_len.assign(prefix_len, prefix_len + n_seqs);
+    p.suffix_len.assign(suffix_len, suffix_len + n_seqs);
+    p.ctx_len.resize(n_seqs);
+    p.n_prefix_pages.resize(n_seqs);
+    p.n_suffix_pages.resize(n_seqs);
+    p.block_table.assign((size_t)n_seqs * bt_row_stride, -1);
+
+    // ---- validation + per-sequence integers
+    for (int s = 0; s < n_seqs; ++s) {
+        const int64_t pl = prefix_len[s], sl = suffix_len[s];
+        if (pl < 0 || sl < 0) {
+            *err = fmt("sequence %lld: negative length", s);
+            return TAPER_ELEN;
+        }
+        if (pl + sl < 1) {
+            *err = fmt("sequence %lld: empty context", s);
+            return TAPER_ELEN;
+        }
+        if (pl + sl > (1 << 30)) {
+            *err = fmt("sequence %lld: context too long", s);
+            return TAPER_ELEN;
+        }
+        const int64_t npp = (pl + P - 1) / P, nsp = (sl + P - 1) / P;
+        if (npp + nsp > bt_row_stride) {
+            *err = fmt("sequence %lld: needs %lld block-table entries, row has %lld", s, npp + nsp, bt_row_stride);
+            return TAPER_ELEN;
+        }
+        p.ctx_len[s] = (int32_t)(pl + sl);
+        p.n_prefix_pages[s] = (int32_t)npp;
+        p.n_suffix_pages[s] = (int32_t)nsp;
+        const int32_t* row = block_table + (size_t)s * bt_row_stride;
+        for (int j = 0; j < npp + nsp; ++j) {
+            if (row[j] < 0 || row[j] >= n_pool_pages) {
+                *err = fmt("sequence %lld entry %lld: page %lld outside the pool", s, j, row[j]);
+                return TAPER_EBLOCK;
+            }
+            p.block_table[(size_t)s * bt_row_stride + j] = row[j];
+        }
+        p.tokens_logical += pl + sl;
+    }
+    // ---- request CSR
+    for (int s = 0; s < n_seqs; ++s) {
+        if (s == 0) {
+            if (branch_group[0] != 0) {
+                *err = "branch_group must start at 0";
+                return TAPER_EGROUP;
+            }
+            p.group_start.push_back(0);
+        } else if (branch_group[s] == branch_group[s - 1] + 1) {
+            p.group_start.push_back(s);
+        } else if (branch_group[s] != branch_group[s - 1]) {
+            *err = fmt("sequence %lld: branch_group must be non-decreasing in steps of 1", s);
+            return TAPER_EGROUP;
+        }
+    }
+    p.n_groups = (int)p.group_start.size();
+    p.group_start.push_back(n_seqs);
+    for (int gi = 0; gi < p.n_groups; ++gi) {
+        const int a = p.group_start[gi], b = p.group_start[gi + 1];
+        for (int s = a + 1; s < b; ++s) {
+            if (prefix_len[s] != prefix_len[a]) {
+                *err = fmt("sequence %lld: prefix_len differs from its request's first member", s);
+                return TAPER_EGROUP;
+            }
+            if (std::memcmp(block_table + (size_t)s * bt_row_stride, block_table + (size_t)a * bt_row_stride,
+                            sizeof(int32_t) * p.n_prefix_pages[a]) != 0) {
+                *err = fmt("sequence %lld: prefix pages differ from its request's first member", s);
+                return TAPER_EGROUP;
+            }
+        }
+    }
+
+    // ---- segments of KV to stream
+    std::vector<Segment> shared, priv;
+    for (int gi = 0; gi < p.n_groups; ++gi) {
+        const int a = p.group_start[gi], b = p.group_start[gi + 1], B = b - a;
+        const int pl = prefix_len[a];
+        p.tokens_unique += pl;
+        if (pl > 0) {
+            if (B >= 2 && share_prefix) {
+                const int n_sub = (B + cap_branches - 1) / cap_branches;
+                for (int k = 0; k < n_sub; ++k) {  // balanced sub-groups of at most cap_branches
+                    const int lo = a + (int)((int64_t)B * k / n_sub), hi = a + (int)((int64_t)B * (k + 1) / n_sub);
+                    if (hi - lo >= 2)
+                        shared.push_back({lo, hi - lo, 0, pl, 0});
+                    else if (hi - lo == 1)
+                        priv.push_back({lo, 1, 0, pl, 1});
+                }
+            } else {
+                for (int s = a; s < b; ++s) priv.push_back({s, 1, 0, pl, 1});
+            }
+        }
+        for (int s = a; s < b; ++s) {
+            p.tokens_unique += suffix_len[s];
+            if (suffix_len[s] > 0) priv.push_back({s, 1, p.n_prefix_pages[s], suffix_len[s], 1});
+        }
+    }
+
+    // ---- workgroup shares: total parts = target_wgs / Hkv, split between kinds by tokens
+    int64_t tok_shared = 0, tok_priv = 0;
+    for (const Segment& s : shared) tok_shared += s.n_tokens;
+    for (const Segment& s : priv) tok_priv += s.n_tokens;
+    const int parts_total = std::max(1, target_wgs / cfg.n_kv_heads);
+    int want_shared = 0, want_priv = 0;
+    if (tok_shared > 0 && tok_priv > 0) {
+        want_shared = (int)std::max<int64_t>(1, (parts_total * tok_shared + (tok_shared + tok_priv) / 2) / (tok_shared + tok_priv));
+        want_priv = std::max(1, parts_total - want_shared);
+    } else if (tok_shared > 0) {
+        want_shared = parts_total;
+    } else {
+        want_priv = parts_total;
+    }
+    p.n_parts_shared = partition(shared, want_shared, kSharedBlockTokens, 0, &p.items);
+    p.n_parts_private = partition(priv, want_priv, kPrivateBlockTokens, p.n_parts_shared, &p.items);
+    const int n_parts = p.n_parts_shared + p.n_parts_private;
+    p.part_start.assign(n_parts + 1, 0);
+    for (const taper_work_item& it : p.items) p.part_start[it.part + 1]++;
+    for (int i = 0; i < n_parts; ++i) p.part_start[i + 1] += p.part_start[i];
+
+    // ---- partial rows and merge map
+    std::vector<std::vector<taper_merge_entry>> per_seq(n_seqs);
+    int64_t rows = 0;
+    for (taper_work_item& it : p.items) {
+        if (rows + (int64_t)it.n_branch * cfg.n_q_heads > INT32_MAX) {
+            *err = "too many partial rows";
+            return TAPER_EINVAL;
+        }
+        it.part_base = (int32_t)rows;
+        const int rph = it.n_branch * g;
+        if (it.kind == 0) p.max_row_tiles_shared = std::max(p.max_row_tiles_shared, (rph + 15) / 16);
+        for (int b = 0; b < it.n_branch; ++b) per_seq[it.seq0 + b].push_back({it.part_base + b * g, rph});
+        rows += (int64_t)rph * cfg.n_kv_heads;
+    }
+    p.n_partial_rows = rows;
+    p.merge_start.assign(n_seqs + 1, 0);
+    for (int s = 0; s < n_seqs; ++s) {
+        p.merge_start[s + 1] = p.merge_start[s] + (int32_t)per_seq[s].size();
+        p.merge.insert(p.merge.end(), per_seq[s].begin(), per_seq[s].end());
+    }
+    return TAPER_OK;
+}
+
+void resolve_slots_host(const HostPlan& p, int P, int64_t* slots, int64_t stride) {
+    for (int s = 0; s < p.n_seqs; ++s) {
+        const int32_t* row = p.block_table.data() + (size_t)s * p.bt_stride;
+        for (int64_t t = 0; t < stride; ++t) {
+            int64_t v = -1;
+            if (t < p.ctx_len[s]) {
+                if (t < p.prefix_len[s]) {
+                    v = (int64_t)row[t / P] * P + t % P;
+                } else {
+                    const int64_t j = t - p.prefix_len[s];
+                    v = (int64_t)row[p.n_prefix_pages[s] + j / P] * P + j % P;
+                }
+            }
+            slots[(size_t)s * stride + t] = v;
+        }
+    }
+}
+
+}  // namespace taper

@@ -1,0 +1,59 @@
+"""Helpers for the GPU parity tests: move a seeded batch to the device, run the
+library through its C ABI, bring the result back as float64."""
+import numpy as np
+
+import oracle
+from taper_inputs import Batch, f32_from_bf16_bits
+
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3  # parity bar for bf16 inputs / fp32 accumulation
+
+
+def torch_bf16(bits: np.ndarray, device="cuda:0"):
+    import torch
+
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device)
+    return t.view(torch.bfloat16)
+
+
+def bits_from_torch(t) -> np.ndarray:
+    import torch
+
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def run_gpu(ctx, b: Batch, q_dev=None, kv_dev=None, want_lse=True, **plan_kw):
+    """Returns (out float64 [S,Hq,D], lse float64 or None, out bits uint16)."""
+    import torch
+
+    st, sh = b.structure, b.structure.shape
+    q_dev = torch_bf16(b.q) if q_dev is None else q_dev
+    kv_dev = torch_bf16(b.kv) if kv_dev is None else kv_dev
+    out = torch.full((st.n_seqs, sh.n_q_heads, sh.head_dim), float("nan"), dtype=torch.bfloat16, device=q_dev.device)
+    lse = torch.full((st.n_seqs, sh.n_q_heads), float("nan"), dtype=torch.float32, device=q_dev.device) if want_lse else None
+    plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages, **plan_kw)
+    ctx.decode_step_attention(plan, q_dev, kv_dev, out, lse)
+    torch.cuda.synchronize()
+    plan.free()
+    bits = bits_from_torch(out)
+    return (f32_from_bf16_bits(bits).astype(np.float64), lse.double().cpu().numpy() if want_lse else None, bits)
+
+
+def run_oracle(b: Batch, n_threads=0):
+    st, sh = b.structure, b.structure.shape
+    out, lse, _, _ = oracle.attention(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.page_size, sh.scale, b.q, b.kv,
+                                      st.block_table, st.prefix_len, st.suffix_len, n_threads=n_threads)
+    return out, lse
+
+
+def assert_parity(got, ref, what=""):
+    assert np.all(np.isfinite(got)), f"{what}: non-finite output"
+    err = np.abs(got - ref)
+    rms = float(np.sqrt(np.mean(ref ** 2)))
+    mx, mean = float(err.max()), float(err.mean())
+    print(f"[parity] {what}: max_abs={mx:.3e} mean_abs={mean:.3e} rms(ref)={rms:.3e} max_abs/rms={mx / rms:.3e}", flush=True)
+    assert mx <= MAX_ABS, f"{what}: max-abs {mx} > {MAX_ABS}"
+    assert mean <= MEAN_ABS, f"{what}: mean-abs {mean} > {MEAN_ABS}"
+    # the absolute bar is loose for long contexts (outputs shrink like 1/sqrt(n)); bf16 rounding of the
+    # output alone is 2^-9 relative per element, so hold the error to a few percent of the output scale too
+    assert mx <= 0.05 * rms + 1e-6, f"{what}: max-abs {mx} is more than 5% of rms(ref) {rms}"
+    return mx, mean

@@ -1,0 +1,272 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 oracle, element
+by element, on the same seeded inputs.  Bar: max-abs 2e-2, mean-abs 2e-3 for the
+floating-point outputs (bf16 inputs, fp32 accumulation); integers bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+from taper_inputs import (AttnShape, Batch, bf16_bits_from_f32, compact_rows, f32_from_bf16_bits, fill_values_numpy,
+                          structure_config1, structure_config2, structure_config3, structure_custom)
+from tests.gpu_util import assert_parity, bits_from_torch, run_gpu, run_oracle, torch_bf16
+from tests.layout_ref import PoolView
+
+pytestmark = pytest.mark.gpu
+
+QWEN = AttnShape(64, 8, 128, 16)
+TINY = AttnShape(4, 1, 64, 16)
+
+
+@pytest.fixture(scope="module")
+def ctx_qwen():
+    from paper_2605_06914_amd import Context
+
+    c = Context(64, 8, 128, device=0)
+    yield c
+    c.close()
+
+
+@pytest.fixture(scope="module")
+def ctx_tiny():
+    from paper_2605_06914_amd import Context
+
+    c = Context(4, 1, 64, device=0)
+    yield c
+    c.close()
+
+
+def test_library_is_loaded_from_tree():
+    from paper_2605_06914_amd import LIB_PATH, load_library
+
+    load_library()
+    assert any(LIB_PATH in line for line in open("/proc/self/maps"))
+
+
+@pytest.mark.parametrize("share", [True, False])
+def test_config1_tiny(ctx_tiny, share):
+    b = fill_values_numpy(structure_config1())
+    ref, ref_lse = run_oracle(b)
+    got, lse, _ = run_gpu(ctx_tiny, b, share_prefix=share)
+    assert_parity(got, ref, f"config1 share={share}")
+    assert np.max(np.abs(lse - ref_lse)) <= 2e-3
+
+
+RAGGED = [(37, [0]), (50, [0, 7, 16, 21]), (16, [1]), (700, [0, 33, 64, 65, 129, 300]), (1, [0]), (2100, [0]),
+          (0, [45]), (31, [31, 32, 33]), (64, [0, 0]), (129, [1] * 9)]
+
+
+@pytest.mark.parametrize("share,target", [(True, 0), (False, 0), (True, 8), (True, 4096)])
+def test_ragged_qwen_shape(ctx_qwen, share, target):
+    """Several tiles, partial pages, prefixes ending mid-page, empty branches, a
+    suffix-only sequence, one-token context; also under very coarse and very fine
+    workgroup shares."""
+    b = fill_values_numpy(structure_custom(QWEN, RAGGED, seed=101))
+    ref, ref_lse = run_oracle(b)
+    got, lse, _ = run_gpu(ctx_qwen, b, share_prefix=share, target_workgroups=target)
+    assert_parity(got, ref, f"ragged share={share} target={target}")
+    assert np.max(np.abs(lse - ref_lse)) <= 2e-3
+
+
+@pytest.mark.parametrize("width", [2, 3, 16, 17, 24, 25, 40])
+def test_wide_requests(ctx_qwen, width):
+    """Branch widths around the limits of one workgroup's row tiles (16 rows per
+    tile, 12 tiles per workgroup, wider requests cut into sub-groups)."""
+    rng = np.random.default_rng(width)
+    reqs = [(300, [0]), (333, [int(x) for x in rng.integers(0, 40, size=width)])]
+    b = fill_values_numpy(structure_custom(QWEN, reqs, seed=200 + width))
+    ref, _ = run_oracle(b)
+    got, _, _ = run_gpu(ctx_qwen, b)
+    assert_parity(got, ref, f"width={width}")
+
+
+@pytest.mark.parametrize("width", [5, 48, 50])
+def test_wide_requests_tiny_shape(ctx_tiny, width):
+    rng = np.random.default_rng(width)
+    reqs = [(90, [int(x) for x in rng.integers(0, 40, size=width)]), (77, [0])]
+    b = fill_values_numpy(structure_custom(TINY, reqs, seed=300 + width))
+    ref, _ = run_oracle(b)
+    got, _, _ = run_gpu(ctx_tiny, b)
+    assert_parity(got, ref, f"tiny width={width}")
+
+
+def poison(b: Batch, val=1e30):
+    """+-val in every slot no sequence may read."""
+    st, sh = b.structure, b.structure.shape
+    P = sh.page_size
+    valid = np.zeros((st.n_pool_pages, P), bool)
+    for s in range(st.n_seqs):
+        npre, nsuf = int(st.prefix_len[s]), int(st.suffix_len[s])
+        npp = -(-npre // P)
+        for t in range(npre):
+            valid[st.block_table[s, t // P], t % P] = True
+        for j in range(nsuf):
+            valid[st.block_table[s, npp + j // P], j % P] = True
+    pv = PoolView(sh.n_kv_heads, sh.head_dim, P)
+    flat = b.kv.reshape(-1)
+    d = np.arange(sh.head_dim)
+    pos = bf16_bits_from_f32(np.array([val], np.float32))[0]
+    neg = bf16_bits_from_f32(np.array([-val], np.float32))[0]
+    pages, toks = np.nonzero(~valid)
+    for page, tok in zip(pages, toks):
+        for hk in range(sh.n_kv_heads):
+            flat[pv.k_off(page, hk, tok, d)] = np.where(d % 2 == 0, pos, neg)
+            flat[pv.v_off(page, hk, tok, d)] = np.where(d % 2 == 0, neg, pos)
+
+
+def test_garbage_in_invalid_slots_changes_nothing(ctx_qwen):
+    reqs = [(37, [0]), (50, [0, 7, 16, 21]), (16, [1]), (133, [3, 70])]
+    b = fill_values_numpy(structure_custom(QWEN, reqs, seed=102))
+    _, _, bits0 = run_gpu(ctx_qwen, b)
+    poison(b)
+    got, _, bits1 = run_gpu(ctx_qwen, b)
+    ref, _ = run_oracle(b)
+    assert_parity(got, ref, "poisoned")
+    assert np.array_equal(bits0, bits1)
+
+
+def test_run_to_run_bit_identical(ctx_qwen):
+    b = fill_values_numpy(structure_custom(QWEN, RAGGED, seed=103))
+    import torch
+
+    q, kv = torch_bf16(b.q), torch_bf16(b.kv)
+    runs = [run_gpu(ctx_qwen, b, q, kv)[2] for _ in range(3)]
+    assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
+
+
+def test_sibling_independence(ctx_qwen):
+    """Lemma 1: which siblings share the step must not change a branch's output
+    (beyond summation order; the prefix partial is computed per row, so it is in
+    fact bit-identical as long as the chunking of the prefix is the same)."""
+    reqs = [(500, [0]), (900, [5, 60, 0, 17, 130, 40])]
+    b = fill_values_numpy(structure_custom(QWEN, reqs, seed=104))
+    full, _, _ = run_gpu(ctx_qwen, b)
+    ref, _ = run_oracle(b)
+    assert_parity(full, ref, "all siblings")
+    worst = 0.0
+    for keep in ([0, 3], [0, 1, 6], [0, 6, 4, 2]):
+        rows = np.array(sorted(keep))
+        sub, pages = compact_rows(b.structure, rows)
+        bs = Batch(sub, b.q[rows], b.kv[pages])
+        got, _, _ = run_gpu(ctx_qwen, bs)
+        assert_parity(got, ref[rows], f"siblings {keep}")
+        worst = max(worst, float(np.max(np.abs(got - full[rows]))))
+    print(f"[lemma1] max |out(subset) - out(all)| = {worst:.3e}")
+    assert worst <= 4e-3
+
+
+def test_dominant_key_names_the_physical_slot(ctx_qwen):
+    """End-to-end index check through the floating-point path: one key aligned
+    with q takes all the weight and V rows are one-hot codes of (page, token)."""
+    sh = AttnShape(64, 8, 128, 16)
+    st = structure_custom(sh, [(24, [0]), (20, [3, 20])], seed=6, n_pool_pages=7)
+    b = fill_values_numpy(st)
+    pv = PoolView(8, 128, 16)
+    flat = b.kv.reshape(-1)
+    d = np.arange(128)
+    one = bf16_bits_from_f32(np.array([1.0], np.float32))[0]
+    for page in range(7):
+        for tok in range(16):
+            for hk in range(8):
+                flat[pv.v_off(page, hk, tok, d)] = np.where(d == page * 16 + tok, one, 0).astype(np.uint16)
+    rng = np.random.default_rng(0)
+    for s in range(st.n_seqs):
+        npre, nsuf = int(st.prefix_len[s]), int(st.suffix_len[s])
+        for t_star in [int(rng.integers(0, npre))] + ([npre + int(rng.integers(0, nsuf))] if nsuf else []):
+            if t_star < npre:
+                page, tok = int(st.block_table[s, t_star // 16]), t_star % 16
+            else:
+                j = t_star - npre
+                page, tok = int(st.block_table[s, -(-npre // 16) + j // 16]), j % 16
+            h = int(rng.integers(0, 64))
+            qv = f32_from_bf16_bits(b.q[s, h]).astype(np.float64)
+            saved = flat[pv.k_off(page, h // 8, tok, d)].copy()
+            flat[pv.k_off(page, h // 8, tok, d)] = bf16_bits_from_f32((200.0 * qv / np.linalg.norm(qv)).astype(np.float32))
+            got, _, _ = run_gpu(ctx_qwen, b)
+            flat[pv.k_off(page, h // 8, tok, d)] = saved
+            assert int(np.argmax(got[s, h])) == page * 16 + tok
+            assert got[s, h, page * 16 + tok] == 1.0
+            assert np.count_nonzero(got[s, h]) == 1
+
+
+@pytest.mark.parametrize("maker", [structure_config1, lambda: structure_custom(QWEN, RAGGED, seed=101)])
+def test_integer_outputs_bit_exact(maker):
+    import torch
+
+    from paper_2605_06914_amd import Context
+
+    st = maker()
+    sh = st.shape
+    ints = oracle.resolve(sh.page_size, st.block_table, st.branch_group, st.prefix_len, st.suffix_len)
+    ctx = Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, device=0)
+    plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages)
+    e = plan.export()
+    assert e["n_groups"] == ints.n_groups
+    for key in ("ctx_len", "n_prefix_pages", "n_suffix_pages", "group_start"):
+        assert np.array_equal(e[key], getattr(ints, key)), key
+    stride = ints.slots.shape[1]
+    dev = torch.full((st.n_seqs, stride), -7, dtype=torch.int64, device="cuda:0")
+    plan.resolve_slots(dev, stride)
+    torch.cuda.synchronize()
+    assert np.array_equal(dev.cpu().numpy(), ints.slots)
+    assert np.array_equal(plan.resolve_slots_host(stride), ints.slots)
+    plan.free()
+    ctx.close()
+
+
+def test_simple_entry_point(ctx_qwen):
+    import torch
+
+    b = fill_values_numpy(structure_custom(QWEN, RAGGED[:4], seed=105))
+    st = b.structure
+    q, kv = torch_bf16(b.q), torch_bf16(b.kv)
+    out = torch.zeros_like(q)
+    ctx_qwen.decode_step_attention_simple(q, kv, st.n_pool_pages, st.block_table, st.branch_group, st.prefix_len,
+                                          st.suffix_len, out)
+    got = f32_from_bf16_bits(bits_from_torch(out)).astype(np.float64)
+    ref, _ = run_oracle(b)
+    assert_parity(got, ref, "simple entry")
+
+
+def test_step_latency_probe_runs(ctx_qwen):
+    import torch
+
+    b = fill_values_numpy(structure_custom(QWEN, RAGGED, seed=106))
+    st = b.structure
+    q, kv = torch_bf16(b.q), torch_bf16(b.kv)
+    outs = [torch.zeros_like(q) for _ in range(3)]
+    plan = ctx_qwen.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages)
+    res = ctx_qwen.step_latency_probe(plan, [q] * 3, [kv] * 3, outs, warmup=2, iters=5)
+    assert res.n_tokens == st.n_seqs and res.n_layers == 3
+    assert res.l_context == st.logical_tokens
+    assert res.kv_bytes_unique == st.kv_bytes_unique and res.kv_bytes_logical == st.kv_bytes_logical
+    assert 0 < res.us_min <= res.us_median
+    ref, _ = run_oracle(b)
+    for o in outs:
+        assert_parity(f32_from_bf16_bits(bits_from_torch(o)).astype(np.float64), ref, "probe layer")
+    kt = ctx_qwen.kernel_times(plan, q, kv, outs[0], warmup=1, iters=3)
+    assert kt["private_us"] > 0 and kt["merge_us"] > 0
+    plan.free()
+
+
+def test_config2_full_size(ctx_qwen):
+    """IRP-Off batch at full size, default launch configuration, every output."""
+    b = fill_values_numpy(structure_config2())
+    ref, _ = run_oracle(b)
+    got, _, _ = run_gpu(ctx_qwen, b, want_lse=False)
+    assert_parity(got, ref, "config2 full")
+
+
+def test_config3_full_size_sampled(ctx_qwen):
+    """Mixed batch at full size; the oracle checks every serial request's
+    neighbour-free sample: 4 serial sequences and each request's first and last
+    branch (all heads)."""
+    b = fill_values_numpy(structure_config3())
+    st = b.structure
+    got, _, _ = run_gpu(ctx_qwen, b, want_lse=False)
+    rows = [0, 5, 10, 15]
+    for g in range(16, st.n_groups):
+        m = np.flatnonzero(st.branch_group == g)
+        rows += [int(m[0]), int(m[-1])]
+    rows = np.array(sorted(set(rows)))
+    sub, pages = compact_rows(st, rows)
+    ref, _ = run_oracle(Batch(sub, b.q[rows], b.kv[pages]))
+    assert_parity(got[rows], ref, "config3 sampled")
