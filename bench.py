@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-step attention hot path on one MI355X.
+
+A *step* is one decode step of a layer stack over one synthetic batch: the index
+resolution / plan build (once per step, inside the timed region) followed by the
+attention of every layer (shared-prefix kernel, private kernel, merge), each
+layer reading its own KV pool.  Inputs are resident in HBM before the timed
+region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixed|irp_off|long] [--layers L]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="mixed", choices=["mixed", "irp_off", "long", "tiny"])
+    ap.add_argument("--layers", type=int, default=0, help="layers per step (0 = workload default)")
+    ap.add_argument("--target-workgroups", type=int, default=0)
+    ap.add_argument("--no-share", action="store_true", help="every branch streams its prefix itself (for comparison)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-iters", type=int, default=20)
+    return ap.parse_args()
+
+
+def make_structure(name):
+    from taper_inputs import structure_config1, structure_config2, structure_config3, structure_config4
+
+    return {"tiny": structure_config1, "irp_off": structure_config2, "mixed": structure_config3,
+            "long": structure_config4}[name]()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one MI355X: this build has no multi-GPU path (see DESIGN.md, 'How it would shard'); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2605_06914_amd import Context
+    from taper_inputs import compact_rows, f32_from_bf16_bits
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    st = make_structure(args.workload)
+    sh = st.shape
+    # default depth: the 64-layer stack of the model the shape comes from; the long workload's pool is
+    # ~30 GB per layer, so it runs a shallower stack
+    n_layers = args.layers or {"mixed": 64, "irp_off": 64, "long": 4, "tiny": 64}[args.workload]
+    pool_elems = st.n_pool_pages * sh.page_elems
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(st.seed + 1000)
+    qs, kvs, outs = [], [], []
+    for _ in range(n_layers):
+        qs.append(torch.randn((st.n_seqs, sh.n_q_heads, sh.head_dim), generator=gen, device=dev,
+                              dtype=torch.float32).to(torch.bfloat16))
+        kv = torch.empty(pool_elems, device=dev, dtype=torch.bfloat16)
+        chunk = 1 << 28
+        for o in range(0, pool_elems, chunk):
+            n = min(chunk, pool_elems - o)
+            kv[o : o + n] = torch.randn(n, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        kvs.append(kv)
+        outs.append(torch.zeros((st.n_seqs, sh.n_q_heads, sh.head_dim), device=dev, dtype=torch.bfloat16))
+    torch.cuda.synchronize()
+
+    ctx = Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, device=0)
+    plan_kw = dict(target_workgroups=args.target_workgroups, share_prefix=not args.no_share)
+
+    def step():
+        plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages, **plan_kw)
+        for l in range(n_layers):
+            ctx.decode_step_attention(plan, qs[l], kvs[l], outs[l])
+        plan.free()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    bytes_step = (st.kv_bytes_unique + st.qo_bytes) * n_layers
+    value = bytes_step / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel durations (HIP events on the launch stream) and the plan-free probe
+    plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages, **plan_kw)
+    e = plan.export()
+    F = {n: i for i, n in enumerate(e["item_fields"])}
+    tok_shared = int(e["items"][e["items"][:, F["kind"]] == 0, F["n_tokens"]].sum())
+    tok_private = int(e["items"][e["items"][:, F["kind"]] == 1, F["n_tokens"]].sum())
+    kt = {"decode_us": 0.0, "merge_us": 0.0}
+    n_kt = min(n_layers, 8)
+    for l in range(n_kt):
+        r = ctx.kernel_times(plan, qs[l], kvs[l], outs[l], warmup=2, iters=args.kernel_iters)
+        for k in kt:
+            kt[k] += r[k] / n_kt
+    probe = ctx.step_latency_probe(plan, qs, kvs, outs, warmup=2, iters=max(5, args.steps))
+    # the dominant kernel streams every KV token the plan lists, once (a shared prefix once per item)
+    dom_bytes = (tok_shared + tok_private) * sh.kv_bytes_per_token
+    achieved = dom_bytes / (kt["decode_us"] * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "bytes_per_launch": dom_bytes, "avg_launch_us": round(kt["decode_us"], 2),
+                "kernel_us": {k: round(v, 2) for k, v in kt.items()},
+                "workgroups": (e["n_parts_shared"] + e["n_parts_private"]) * sh.n_kv_heads}
+
+    # ---- CPU oracle on a bounded sample of the same workload (rank 0, N=1)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        # whole batch of layer 0 when it is small enough, else serial requests thinned out and the first and
+        # last branch of each parallel request, capped at `budget` logical tokens (~10-30 core-seconds)
+        budget = 2_000_000
+        if st.logical_tokens <= budget:
+            rows = np.arange(st.n_seqs)
+        else:
+            rows = []
+            serial = [s for s in range(st.n_seqs) if np.sum(st.branch_group == st.branch_group[s]) == 1]
+            rows += serial[:: max(1, len(serial) // 8)][:8]
+            for g in range(st.n_groups):
+                m = np.flatnonzero(st.branch_group == g)
+                if len(m) > 1:
+                    rows += [int(m[0]), int(m[-1])]
+            rows = np.array(sorted(set(rows)))
+            ctxlen = (st.prefix_len + st.suffix_len)[rows]
+            keep = np.cumsum(ctxlen) <= budget
+            keep[0] = True
+            rows = rows[keep]
+        sub, pages = compact_rows(st, rows)
+        pg = torch.from_numpy(pages).to(dev)
+        kv_host = kvs[0].view(st.n_pool_pages, sh.page_elems)[pg].view(torch.int16).cpu().numpy().view(np.uint16)
+        q_host = qs[0][torch.from_numpy(rows).to(dev)].view(torch.int16).cpu().numpy().view(np.uint16)
+        t1 = time.perf_counter()
+        ref, _, _, used = oracle.attention(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.page_size, sh.scale, q_host,
+                                           kv_host, sub.block_table, sub.prefix_len, sub.suffix_len, want_lse=False)
+        t_cpu = time.perf_counter() - t1
+        # same rows from the GPU run of layer 0 (outs[0] holds the last step's result)
+        ctx.decode_step_attention(plan, qs[0], kvs[0], outs[0])
+        torch.cuda.synchronize()
+        got = f32_from_bf16_bits(outs[0][torch.from_numpy(rows).to(dev)].view(torch.int16).cpu().numpy().view(np.uint16))
+        err = np.abs(got.astype(np.float64) - ref)
+        scale_up = st.logical_tokens / sub.logical_tokens
+        t_full = t_cpu * scale_up  # one layer of the full batch, no prefix sharing in the oracle
+        cpu = {"value": round((st.kv_bytes_unique + st.qo_bytes) / t_full / 1e9, 4), "unit": "GB/s", "cores": int(used),
+               "kind": "oracle",
+               "sample": f"{len(rows)} of {st.n_seqs} sequences of layer 0 (whole batch if at most {budget} logical tokens, "
+                         f"else thinned serial requests plus first and last branch of each parallel request), all heads: "
+                         f"{sub.logical_tokens} logical tokens in {t_cpu:.2f} s; scaled by {scale_up:.2f} "
+                         f"(logical tokens of the batch / of the sample) to one layer",
+               "max_abs_err_gpu_vs_oracle": float(err.max()), "mean_abs_err_gpu_vs_oracle": float(err.mean())}
+        assert err.max() <= 2e-2 and err.mean() <= 2e-3, "GPU result of the benchmarked workload is off the oracle"
+    plan.free()
+
+    line = {
+        "metric": "decode_step_attention_effective_kv_bandwidth",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{st.name} x {n_layers} layers (Qwen3-32B attention shape: {sh.n_q_heads} q heads, "
+                               f"{sh.n_kv_heads} kv heads, head_dim {sh.head_dim}, page {sh.page_size}; plan built once "
+                               f"per step inside the timed region; one KV pool per layer)",
+                   "n_layers": n_layers, "n_seqs": st.n_seqs, "n_requests": st.n_groups,
+                   "admitted_branches": int(st.n_seqs - st.n_groups),
+                   "tokens_unique": st.unique_tokens, "tokens_logical": st.logical_tokens,
+                   "kv_bytes_unique_per_layer": st.kv_bytes_unique, "kv_bytes_logical_per_layer": st.kv_bytes_logical,
+                   "share_prefix": not args.no_share},
+        "us_per_layer": round(ms_per_step * 1e3 / n_layers, 2),
+        "frac_of_hbm_peak_whole_step": round(value / HBM_PEAK_GBPS, 4),
+        "logical_gbps": round(st.kv_bytes_logical * n_layers / (ms_per_step * 1e-3) / 1e9, 1),
+        "probe": {"us_per_layer_median": round(probe.us_median / n_layers, 2),
+                  "us_per_layer_min": round(probe.us_min / n_layers, 2), "gbps_unique": round(probe.gbps_unique, 1)},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -143,6 +143,8 @@ TAPER_API void taper_destroy(taper_ctx *ctx);
  * `hip_stream` (unless the context is host-only) and grows the context's
  * workspace if needed.  The host arrays are only read during the call.  One plan
  * serves every layer of the step.  Not safe to call concurrently on one ctx.
+ * Plans must be freed before their context is destroyed; a freed plan's buffers
+ * are recycled by later plans of the same context, ordered on the stream.
  * opts may be NULL.
  */
 TAPER_API int taper_plan_build(taper_ctx *ctx, int n_seqs, const int32_t *block_table /* host */, int bt_row_stride,
@@ -210,9 +212,10 @@ TAPER_API int taper_step_latency_probe(taper_ctx *ctx, const taper_plan *plan, i
                              void *hip_stream, taper_probe_result *result /* host */);
 
 /*
- * Per-kernel timing of one step's launches with HIP events on `hip_stream`
- * (synchronises).  us[0] = shared-prefix kernel, us[1] = private/serial kernel,
- * us[2] = merge kernel; mean over `iters` steps after `warmup`.
+ * Per-kernel timing of one layer's launches with HIP events on `hip_stream`
+ * (synchronises).  us[0] = decode kernel (shared-prefix and private work in one
+ * launch), us[1] = merge kernel, us[2] = their sum; means over `iters` runs
+ * after `warmup`.
  */
 TAPER_API int taper_kernel_times(taper_ctx *ctx, const taper_plan *plan, const void *q, const void *kv_pages, void *out,
                        int warmup, int iters, void *hip_stream, double us[3] /* host */);

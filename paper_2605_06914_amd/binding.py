@@ -142,9 +142,10 @@ class Plan:
         self.ctx, self._h = ctx, handle
 
     def free(self):
-        if self._h:
+        # a plan hands its buffers back to its context, so it must be freed first
+        if self._h and self.ctx._h:
             load_library().taper_plan_free(self._h)
-            self._h = 0
+        self._h = 0
 
     def __del__(self):
         try:
@@ -246,4 +247,4 @@ class Context:
         us = (ctypes.c_double * 3)()
         _check(load_library().taper_kernel_times(self._h, plan._h, _ptr(q), _ptr(kv_pages), _ptr(out), warmup, iters,
                                                  _stream(stream), us))
-        return dict(shared_us=us[0], private_us=us[1], merge_us=us[2])
+        return dict(decode_us=us[0], merge_us=us[1], total_us=us[2])

@@ -33,20 +33,28 @@ int fail_hip(hipError_t e, const char* what) {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 }  // namespace
 
+// Device + pinned-host buffers of a plan.  They are recycled through the context
+// so that a steady-state decode loop neither allocates nor frees (hipFree would
+// synchronise the device once per step).
+struct PlanBuffers {
+    void* dev = nullptr;      // one device allocation holding every integer array
+    void* staging = nullptr;  // pinned host image of `dev`
+    size_t bytes = 0;
+    hipEvent_t uploaded = nullptr;  // recorded after the host-to-device copy
+};
+
 struct taper_ctx {
     taper_attn_config cfg;
     bool host_only = false;
     void* ws = nullptr;  // partials workspace: [rows] float2 (m, l) then [rows][D] float
     int64_t ws_rows = 0;
+    std::vector<PlanBuffers> free_buffers;
 };
 
 struct taper_plan {
     taper_ctx* ctx = nullptr;
     taper::HostPlan host;
-    void* dev = nullptr;          // one device allocation holding every integer array
-    void* staging = nullptr;      // pinned host image of `dev`
-    size_t dev_bytes = 0;
-    hipEvent_t uploaded = nullptr;
+    PlanBuffers buf;
     // device pointers into `dev`
     const int32_t* d_bt = nullptr;
     const taper_work_item* d_items = nullptr;
@@ -59,6 +67,42 @@ struct taper_plan {
 };
 
 namespace {
+
+void destroy_buffers(PlanBuffers& b) {
+    if (b.uploaded) {
+        (void)hipEventSynchronize(b.uploaded);
+        (void)hipEventDestroy(b.uploaded);
+    }
+    if (b.dev) (void)hipFree(b.dev);
+    if (b.staging) (void)hipHostFree(b.staging);
+    b = PlanBuffers();
+}
+
+// Takes a recycled buffer set of at least `bytes`, or allocates one.
+int acquire_buffers(taper_ctx* ctx, size_t bytes, PlanBuffers* out) {
+    for (size_t i = 0; i < ctx->free_buffers.size(); ++i) {
+        if (ctx->free_buffers[i].bytes >= bytes) {
+            *out = ctx->free_buffers[i];
+            ctx->free_buffers.erase(ctx->free_buffers.begin() + i);
+            // the pinned image is about to be overwritten: its last copy must have finished
+            hipError_t e = hipEventSynchronize(out->uploaded);
+            if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
+            return TAPER_OK;
+        }
+    }
+    PlanBuffers b;
+    b.bytes = align_up(bytes + bytes / 2, 4096);
+    hipError_t e = hipHostMalloc(&b.staging, b.bytes, hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMalloc(&b.dev, b.bytes);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&b.uploaded, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        g_last_error = std::string("plan allocation: ") + hipGetErrorString(e);
+        destroy_buffers(b);
+        return TAPER_ENOMEM;
+    }
+    *out = b;
+    return TAPER_OK;
+}
 
 int ensure_workspace(taper_ctx* ctx, int64_t rows) {
     if (rows <= ctx->ws_rows) return TAPER_OK;
@@ -114,14 +158,13 @@ taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const vo
 int check_step(const taper_ctx* ctx, const taper_plan* plan) {
     if (!ctx || !plan) return fail(TAPER_EINVAL, "null ctx or plan");
     if (plan->ctx != ctx) return fail(TAPER_EINVAL, "plan was built on another context");
-    if (ctx->host_only || !plan->dev) return fail(TAPER_EHIP, "host-only context: no device work possible");
+    if (ctx->host_only || !plan->buf.dev) return fail(TAPER_EHIP, "host-only context: no device work possible");
     if (plan->host.n_partial_rows > ctx->ws_rows) return fail(TAPER_EINVAL, "workspace smaller than the plan needs");
     return TAPER_OK;
 }
 
 int enqueue_step(const taper::StepArgs& a, hipStream_t s) {
-    HIP_TRY(taper::launch_shared(a, s));
-    HIP_TRY(taper::launch_private(a, s));
+    HIP_TRY(taper::launch_decode(a, s));
     HIP_TRY(taper::launch_merge(a, s));
     return TAPER_OK;
 }
@@ -173,10 +216,9 @@ int taper_create(const taper_attn_config* cfg, taper_ctx** out_ctx) {
 
 void taper_destroy(taper_ctx* ctx) {
     if (!ctx) return;
-    if (ctx->ws) {
-        (void)hipDeviceSynchronize();
-        (void)hipFree(ctx->ws);
-    }
+    if (!ctx->host_only) (void)hipDeviceSynchronize();
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    for (PlanBuffers& b : ctx->free_buffers) destroy_buffers(b);
     delete ctx;
 }
 
@@ -220,26 +262,26 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
         p.off = total;
         total += align_up(std::max<size_t>(p.bytes, 16), 256);
     }
-    plan->dev_bytes = total;
     hipError_t e = hipSetDevice(ctx->cfg.device);
-    if (e == hipSuccess) e = hipHostMalloc(&plan->staging, total, hipHostMallocDefault);
-    if (e == hipSuccess) e = hipMalloc(&plan->dev, total);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&plan->uploaded, hipEventDisableTiming);
     if (e != hipSuccess) {
-        std::string msg = std::string("plan allocation: ") + hipGetErrorString(e);
-        taper_plan_free(plan);
-        return fail(TAPER_ENOMEM, msg);
+        delete plan;
+        return fail_hip(e, "hipSetDevice");
     }
-    for (const Piece& p : pieces) std::memcpy((char*)plan->staging + p.off, p.src, p.bytes);
+    st = acquire_buffers(ctx, total, &plan->buf);
+    if (st != TAPER_OK) {
+        delete plan;
+        return st;
+    }
+    for (const Piece& p : pieces) std::memcpy((char*)plan->buf.staging + p.off, p.src, p.bytes);
     hipStream_t s = (hipStream_t)hip_stream;
-    e = hipMemcpyAsync(plan->dev, plan->staging, total, hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipEventRecord(plan->uploaded, s);
+    e = hipMemcpyAsync(plan->buf.dev, plan->buf.staging, total, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipEventRecord(plan->buf.uploaded, s);
     if (e != hipSuccess) {
         std::string msg = std::string("plan upload: ") + hipGetErrorString(e);
         taper_plan_free(plan);
         return fail(TAPER_EHIP, msg);
     }
-    char* d = (char*)plan->dev;
+    char* d = (char*)plan->buf.dev;
     plan->d_bt = (const int32_t*)(d + pieces[0].off);
     plan->d_items = (const taper_work_item*)(d + pieces[1].off);
     plan->d_part_start = (const int32_t*)(d + pieces[2].off);
@@ -260,12 +302,10 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
 
 void taper_plan_free(taper_plan* plan) {
     if (!plan) return;
-    if (plan->uploaded) {
-        (void)hipEventSynchronize(plan->uploaded);  // the pinned image must outlive the copy
-        (void)hipEventDestroy(plan->uploaded);
-    }
-    if (plan->dev) (void)hipFree(plan->dev);  // hipFree waits for work that may still read it
-    if (plan->staging) (void)hipHostFree(plan->staging);
+    // Buffers go back to the context.  Work already enqueued that reads them stays
+    // valid: a later plan's upload into the same memory is ordered behind it on the
+    // stream (one stream per context).
+    if (plan->buf.dev) plan->ctx->free_buffers.push_back(plan->buf);
     delete plan;
 }
 
@@ -394,19 +434,17 @@ int taper_kernel_times(taper_ctx* ctx, const taper_plan* plan, const void* q, co
     if (!q || !kv_pages || !out || !us || iters < 1 || warmup < 0) return fail(TAPER_EINVAL, "bad argument");
     hipStream_t s = (hipStream_t)hip_stream;
     const taper::StepArgs a = make_args(ctx, plan, q, kv_pages, out, nullptr);
-    std::vector<hipEvent_t> ev(4 * (size_t)iters, nullptr);
+    std::vector<hipEvent_t> ev(3 * (size_t)iters, nullptr);
     for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
     int rc = TAPER_OK;
     for (int i = 0; i < warmup + iters && rc == TAPER_OK; ++i) {
         const int k = i - warmup;
         hipError_t e = hipSuccess;
-        if (k >= 0) e = hipEventRecord(ev[4 * k], s);
-        if (e == hipSuccess) e = taper::launch_shared(a, s);
-        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[4 * k + 1], s);
-        if (e == hipSuccess) e = taper::launch_private(a, s);
-        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[4 * k + 2], s);
+        if (k >= 0) e = hipEventRecord(ev[3 * k], s);
+        if (e == hipSuccess) e = taper::launch_decode(a, s);
+        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[3 * k + 1], s);
         if (e == hipSuccess) e = taper::launch_merge(a, s);
-        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[4 * k + 3], s);
+        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[3 * k + 2], s);
         if (e != hipSuccess) rc = fail_hip(e, "kernel timing enqueue");
     }
     hipError_t es = hipStreamSynchronize(s);
@@ -414,15 +452,16 @@ int taper_kernel_times(taper_ctx* ctx, const taper_plan* plan, const void* q, co
     double acc[3] = {0, 0, 0};
     if (rc == TAPER_OK) {
         for (int k = 0; k < iters && rc == TAPER_OK; ++k)
-            for (int j = 0; j < 3; ++j) {
+            for (int j = 0; j < 2; ++j) {
                 float ms = 0.f;
-                if (hipEventElapsedTime(&ms, ev[4 * k + j], ev[4 * k + j + 1]) != hipSuccess) {
+                if (hipEventElapsedTime(&ms, ev[3 * k + j], ev[3 * k + j + 1]) != hipSuccess) {
                     rc = fail(TAPER_EHIP, "hipEventElapsedTime");
                     break;
                 }
                 acc[j] += ms * 1000.0;
             }
     }
+    acc[2] = acc[0] + acc[1];
     for (auto& e : ev) (void)hipEventDestroy(e);
     if (rc != TAPER_OK) return rc;
     for (int j = 0; j < 3; ++j) us[j] = acc[j] / iters;

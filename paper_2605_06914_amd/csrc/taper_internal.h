@@ -32,8 +32,7 @@ struct StepArgs {
     float scale_log2e;         // scale * log2(e)
 };
 
-hipError_t launch_shared(const StepArgs& a, hipStream_t s);
-hipError_t launch_private(const StepArgs& a, hipStream_t s);
+hipError_t launch_decode(const StepArgs& a, hipStream_t s);
 hipError_t launch_merge(const StepArgs& a, hipStream_t s);
 hipError_t launch_resolve_slots(const StepArgs& a, int64_t* slots, int64_t stride, hipStream_t s);
 

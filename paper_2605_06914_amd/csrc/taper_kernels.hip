@@ -87,17 +87,20 @@ struct KVRegs {
 };
 
 template <int D>
-__global__ __launch_bounds__(256, 2) void private_kernel(StepArgs a) {
-    constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D, OST = D + 4;
-    __shared__ __attribute__((aligned(16))) float sm_o[4][16][OST];
-    __shared__ float2 sm_ml[4][16];
+struct PrivateSmem {
+    float o[4][16][D + 4];
+    float2 ml[4][16];
+};
 
+template <int D>
+DEV void private_path(const StepArgs& a, const int part, const int hk, PrivateSmem<D>& sm) {
+    constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D;
+    auto& sm_o = sm.o;
+    auto& sm_ml = sm.ml;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15, qd = lane >> 4;
     const int Hkv = a.n_kv_heads, g = a.gqa;
-    const int part = a.n_parts_shared + blockIdx.x / Hkv;
-    const int hk = blockIdx.x % Hkv;
     const __bf16* __restrict__ kvb = (const __bf16*)a.kv;
     const int64_t page_elems = 2LL * Hkv * TILE;
     const float c = a.scale_log2e;
@@ -210,22 +213,27 @@ __global__ __launch_bounds__(256, 2) void private_kernel(StepArgs a) {
 // query rows of all n_branch admitted branches x g heads.  16-row tiles are
 // dealt round-robin to the four waves, up to NTW tiles per wave.
 // ---------------------------------------------------------------------------
-template <int D, int NTW>
-__global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void shared_kernel(StepArgs a) {
-    constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D;
-    constexpr int QE = 4 * D;             // elements of one 4-token quarter of a V tile
-    constexpr int VQ = QE + 64;           // padded quarter: odd multiple of 128 B -> quarters alternate bank halves
-    constexpr int PAGE_LDS = TILE + 4 * VQ;
-    constexpr int BUF = 4 * PAGE_LDS;     // 4 pages = 64 tokens
-    __shared__ __attribute__((aligned(16))) __bf16 lds[2 * BUF];
+template <int D>
+struct SharedSmem {
+    static constexpr int TILE = 16 * D;
+    static constexpr int QE = 4 * D;        // elements of one 4-token quarter of a V tile
+    static constexpr int VQ = QE + 64;      // padded quarter: odd multiple of 128 B -> quarters alternate bank halves
+    static constexpr int PAGE_LDS = TILE + 4 * VQ;
+    static constexpr int BUF = 4 * PAGE_LDS;  // 4 pages = 64 tokens
+    __bf16 kv[2 * BUF];
+};
 
+template <int D, int NTW>
+DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem<D>& sm) {
+    constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D;
+    constexpr int QE = SharedSmem<D>::QE, VQ = SharedSmem<D>::VQ, PAGE_LDS = SharedSmem<D>::PAGE_LDS,
+                  BUF = SharedSmem<D>::BUF;
+    __bf16* lds = sm.kv;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, qd = lane >> 4;
     const int Hkv = a.n_kv_heads, g = a.gqa;
-    const int part = blockIdx.x / Hkv;
-    const int hk = blockIdx.x % Hkv;
     const __bf16* __restrict__ kvb = (const __bf16*)a.kv;
     const int64_t page_elems = 2LL * Hkv * TILE;
     const float c = a.scale_log2e;
@@ -357,6 +365,25 @@ __global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void shared_kernel(StepArg
 }
 
 // ---------------------------------------------------------------------------
+// One launch per layer: workgroup (share, kv head).  Shares below n_parts_shared
+// stream shared prefixes, the others private tokens; both kinds run side by side.
+// ---------------------------------------------------------------------------
+template <int D, int NTW>
+__global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void decode_kernel(StepArgs a) {
+    union Smem {
+        SharedSmem<D> sh;
+        PrivateSmem<D> pr;
+    };
+    __shared__ __attribute__((aligned(16))) char smem_raw[sizeof(Smem)];
+    const int part = blockIdx.x / a.n_kv_heads;
+    const int hk = blockIdx.x % a.n_kv_heads;
+    if (part < a.n_parts_shared)
+        shared_path<D, NTW>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
+    else
+        private_path<D>(a, part, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
+}
+
+// ---------------------------------------------------------------------------
 // Log-sum-exp merge of a sequence's partials (its request's prefix chunks and
 // its own private chunks), normalisation and rounding to bf16.
 // ---------------------------------------------------------------------------
@@ -410,32 +437,24 @@ __global__ __launch_bounds__(256) void resolve_slots_kernel(StepArgs a, int64_t*
 }
 
 // ---------------------------------------------------------------------------
-hipError_t launch_shared(const StepArgs& a, hipStream_t s) {
-    if (a.n_parts_shared == 0) return hipSuccess;
-    const dim3 grid(a.n_parts_shared * a.n_kv_heads), block(256);
-    const int ntw = (a.max_row_tiles_shared + 3) / 4;
+hipError_t launch_decode(const StepArgs& a, hipStream_t s) {
+    const int n_parts = a.n_parts_shared + a.n_parts_private;
+    if (n_parts == 0) return hipSuccess;
+    const dim3 grid(n_parts * a.n_kv_heads), block(256);
+    const int ntw = a.n_parts_shared ? (a.max_row_tiles_shared + 3) / 4 : 1;
     if (a.head_dim == 128) {
-        if (ntw <= 1) hipLaunchKernelGGL((shared_kernel<128, 1>), grid, block, 0, s, a);
-        else if (ntw == 2) hipLaunchKernelGGL((shared_kernel<128, 2>), grid, block, 0, s, a);
-        else if (ntw == 3) hipLaunchKernelGGL((shared_kernel<128, 3>), grid, block, 0, s, a);
+        if (ntw <= 1) hipLaunchKernelGGL((decode_kernel<128, 1>), grid, block, 0, s, a);
+        else if (ntw == 2) hipLaunchKernelGGL((decode_kernel<128, 2>), grid, block, 0, s, a);
+        else if (ntw == 3) hipLaunchKernelGGL((decode_kernel<128, 3>), grid, block, 0, s, a);
         else return hipErrorInvalidValue;
     } else if (a.head_dim == 64) {
-        if (ntw <= 1) hipLaunchKernelGGL((shared_kernel<64, 1>), grid, block, 0, s, a);
-        else if (ntw == 2) hipLaunchKernelGGL((shared_kernel<64, 2>), grid, block, 0, s, a);
-        else if (ntw == 3) hipLaunchKernelGGL((shared_kernel<64, 3>), grid, block, 0, s, a);
+        if (ntw <= 1) hipLaunchKernelGGL((decode_kernel<64, 1>), grid, block, 0, s, a);
+        else if (ntw == 2) hipLaunchKernelGGL((decode_kernel<64, 2>), grid, block, 0, s, a);
+        else if (ntw == 3) hipLaunchKernelGGL((decode_kernel<64, 3>), grid, block, 0, s, a);
         else return hipErrorInvalidValue;
     } else {
         return hipErrorInvalidValue;
     }
-    return hipGetLastError();
-}
-
-hipError_t launch_private(const StepArgs& a, hipStream_t s) {
-    if (a.n_parts_private == 0) return hipSuccess;
-    const dim3 grid(a.n_parts_private * a.n_kv_heads), block(256);
-    if (a.head_dim == 128) hipLaunchKernelGGL((private_kernel<128>), grid, block, 0, s, a);
-    else if (a.head_dim == 64) hipLaunchKernelGGL((private_kernel<64>), grid, block, 0, s, a);
-    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

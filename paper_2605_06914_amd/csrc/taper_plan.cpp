@@ -50,17 +50,16 @@ struct Segment {
     int32_t seq0, n_branch, page0, n_tokens, kind;
 };
 
-// Cut `segs` into at most n_parts workgroup shares of about equal token count, at
+// Cut `segs` into workgroup shares of about `quota` blocks of `blk` tokens, at
 // multiples of `blk` tokens from each segment's start.  Appends items (tagged
 // with part ids starting at part_id0) and returns the number of shares used.
-int partition(const std::vector<Segment>& segs, int n_parts, int blk, int part_id0,
+int partition(const std::vector<Segment>& segs, int64_t quota, int blk, int part_id0,
               std::vector<taper_work_item>* items) {
     int64_t total_blocks = 0;
     for (const Segment& s : segs) total_blocks += (s.n_tokens + blk - 1) / blk;
     if (total_blocks == 0) return 0;
-    n_parts = (int)std::max<int64_t>(1, std::min<int64_t>(n_parts, total_blocks));
-    const int64_t quota = (total_blocks + n_parts - 1) / n_parts;
-    const int64_t sliver = std::max<int64_t>(1, quota / 8);
+    quota = std::max<int64_t>(1, quota);
+    const int64_t sliver = std::max<int64_t>(1, quota / 32);  // an item's fixed cost is about one block's time
     int part = 0;
     int64_t fill = 0;
     for (const Segment& s : segs) {
@@ -225,22 +224,21 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
         }
     }
 
-    // ---- workgroup shares: total parts = target_wgs / Hkv, split between kinds by tokens
-    int64_t tok_shared = 0, tok_priv = 0;
-    for (const Segment& s : shared) tok_shared += s.n_tokens;
-    for (const Segment& s : priv) tok_priv += s.n_tokens;
+    // ---- workgroup shares: both kinds run in one launch, so every share gets about the same
+    // number of tokens: total tokens / (target_wgs / Hkv), rounded up to whole 64-token blocks
+    int64_t tok_total = 0;
+    for (const Segment& s : shared) tok_total += s.n_tokens;
+    for (const Segment& s : priv) tok_total += s.n_tokens;
     const int parts_total = std::max(1, target_wgs / cfg.n_kv_heads);
-    int want_shared = 0, want_priv = 0;
-    if (tok_shared > 0 && tok_priv > 0) {
-        want_shared = (int)std::max<int64_t>(1, (parts_total * tok_shared + (tok_shared + tok_priv) / 2) / (tok_shared + tok_priv));
-        want_priv = std::max(1, parts_total - want_shared);
-    } else if (tok_shared > 0) {
-        want_shared = parts_total;
-    } else {
-        want_priv = parts_total;
+    int64_t quota_tokens = (tok_total + parts_total - 1) / parts_total;
+    quota_tokens = std::max<int64_t>(kSharedBlockTokens, (quota_tokens + kSharedBlockTokens - 1) / kSharedBlockTokens * kSharedBlockTokens);
+    for (;;) {  // never more shares than asked for: an extra one would run after all the others
+        p.items.clear();
+        p.n_parts_shared = partition(shared, quota_tokens / kSharedBlockTokens, kSharedBlockTokens, 0, &p.items);
+        p.n_parts_private = partition(priv, quota_tokens / kPrivateBlockTokens, kPrivateBlockTokens, p.n_parts_shared, &p.items);
+        if (p.n_parts_shared + p.n_parts_private <= parts_total || quota_tokens >= tok_total) break;
+        quota_tokens += kSharedBlockTokens;
     }
-    p.n_parts_shared = partition(shared, want_shared, kSharedBlockTokens, 0, &p.items);
-    p.n_parts_private = partition(priv, want_priv, kPrivateBlockTokens, p.n_parts_shared, &p.items);
     const int n_parts = p.n_parts_shared + p.n_parts_private;
     p.part_start.assign(n_parts + 1, 0);
     for (const taper_work_item& it : p.items) p.part_start[it.part + 1]++;
