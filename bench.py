@@ -3,7 +3,7 @@
 
 A *step* is one decode step of a layer stack over one synthetic batch: the index
 resolution / plan build (once per step, inside the timed region) followed by the
-attention of every layer (shared-prefix kernel, private kernel, merge), each
+attention of every layer (one launch: shared-prefix work, private work, merge), each
 layer reading its own KV pool.  Inputs are resident in HBM before the timed
 region starts.  Prints ONE JSON line.
 
@@ -33,6 +33,7 @@ def parse():
     ap.add_argument("--workload", default="mixed", choices=["mixed", "irp_off", "long", "tiny"])
     ap.add_argument("--layers", type=int, default=0, help="layers per step (0 = workload default)")
     ap.add_argument("--target-workgroups", type=int, default=0)
+    ap.add_argument("--shared-cost-pct", type=int, default=0)
     ap.add_argument("--no-share", action="store_true", help="every branch streams its prefix itself (for comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=20)
@@ -81,7 +82,8 @@ def main():
     torch.cuda.synchronize()
 
     ctx = Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, device=0)
-    plan_kw = dict(target_workgroups=args.target_workgroups, share_prefix=not args.no_share)
+    plan_kw = dict(target_workgroups=args.target_workgroups, share_prefix=not args.no_share,
+                   shared_cost_pct=args.shared_cost_pct)
 
     def step():
         plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages, **plan_kw)
@@ -107,7 +109,7 @@ def main():
     F = {n: i for i, n in enumerate(e["item_fields"])}
     tok_shared = int(e["items"][e["items"][:, F["kind"]] == 0, F["n_tokens"]].sum())
     tok_private = int(e["items"][e["items"][:, F["kind"]] == 1, F["n_tokens"]].sum())
-    kt = {"decode_us": 0.0, "merge_us": 0.0}
+    kt = {"decode_us": 0.0, "decode_us_min": 0.0}
     n_kt = min(n_layers, 8)
     for l in range(n_kt):
         r = ctx.kernel_times(plan, qs[l], kvs[l], outs[l], warmup=2, iters=args.kernel_iters)

@@ -129,7 +129,8 @@ typedef struct {
     int32_t share_prefix;      /* 1 = default: read each request's prefix once for all its
                                   branches; 0 = every branch streams the prefix by itself  */
     int32_t max_branches_per_item; /* 0 = default (24); wider requests are cut into sub-groups */
-    int32_t reserved;
+    int32_t shared_cost_pct;   /* 0 = default (130): relative cost of a shared-prefix token when
+                                  cutting the work into equal shares                           */
 } taper_plan_options;
 
 TAPER_API int taper_create(const taper_attn_config *cfg /* host */, taper_ctx **out_ctx);
@@ -169,7 +170,7 @@ TAPER_API int taper_plan_resolve_slots(taper_ctx *ctx, const taper_plan *plan, i
  * The hot call (paper §1/§2.3 decode step; §3.1 visibility rule): for every
  * sequence s and query head h,
  *     out[s,h,:] = sum_t softmax_t(scale * q[s,h,:].K_t) V_t
- * over t in shared prefix ++ private tokens of s.  Enqueues kernels on
+ * over t in shared prefix ++ private tokens of s.  Enqueues one kernel on
  * `hip_stream` and returns; allocates nothing, does not synchronise.  q, kv_pages,
  * out (and lse if not NULL) are device pointers owned by the caller and must stay
  * valid until the stream has run the work.  Calls on one ctx share its workspace
@@ -212,13 +213,13 @@ TAPER_API int taper_step_latency_probe(taper_ctx *ctx, const taper_plan *plan, i
                              void *hip_stream, taper_probe_result *result /* host */);
 
 /*
- * Per-kernel timing of one layer's launches with HIP events on `hip_stream`
- * (synchronises).  us[0] = decode kernel (shared-prefix and private work in one
- * launch), us[1] = merge kernel, us[2] = their sum; means over `iters` runs
- * after `warmup`.
+ * Duration of the decode kernel (the one launch a layer's attention consists of:
+ * shared-prefix work, private work and the merge of partials) measured with HIP
+ * events on `hip_stream` (synchronises).  us[0] = mean, us[1] = minimum over
+ * `iters` launches after `warmup`.
  */
 TAPER_API int taper_kernel_times(taper_ctx *ctx, const taper_plan *plan, const void *q, const void *kv_pages, void *out,
-                       int warmup, int iters, void *hip_stream, double us[3] /* host */);
+                       int warmup, int iters, void *hip_stream, double us[2] /* host */);
 
 TAPER_API const char *taper_strerror(int status);
 TAPER_API const char *taper_last_error(void);

@@ -55,7 +55,7 @@ class taper_plan_view(ctypes.Structure):
 
 class taper_plan_options(ctypes.Structure):
     _fields_ = [("target_workgroups", ctypes.c_int32), ("share_prefix", ctypes.c_int32),
-                ("max_branches_per_item", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("max_branches_per_item", ctypes.c_int32), ("shared_cost_pct", ctypes.c_int32)]
 
 
 class taper_probe_result(ctypes.Structure):
@@ -207,12 +207,12 @@ class Context:
 
     def plan_build(self, block_table, branch_group, prefix_len, suffix_len, n_pool_pages: int,
                    target_workgroups: int = 0, share_prefix: bool = True, max_branches_per_item: int = 0,
-                   stream=None) -> Plan:
+                   shared_cost_pct: int = 0, stream=None) -> Plan:
         bt = _i32(block_table)
         grp, pl, sl = _i32(branch_group), _i32(prefix_len), _i32(suffix_len)
         if bt.ndim != 2 or not (len(grp) == len(pl) == len(sl) == bt.shape[0]):
             raise TaperError(TAPER_EINVAL, "block_table must be [S, max_blocks] and the per-sequence arrays length S")
-        opts = taper_plan_options(target_workgroups, int(share_prefix), max_branches_per_item, 0)
+        opts = taper_plan_options(target_workgroups, int(share_prefix), max_branches_per_item, shared_cost_pct)
         h = ctypes.c_void_p()
         st = 0 if self.cfg.device < 0 else _stream(stream)
         _check(load_library().taper_plan_build(self._h, bt.shape[0], bt.ctypes.data, bt.shape[1], grp.ctypes.data,
@@ -244,7 +244,7 @@ class Context:
         return res
 
     def kernel_times(self, plan: Plan, q, kv_pages, out, warmup: int = 5, iters: int = 20, stream=None):
-        us = (ctypes.c_double * 3)()
+        us = (ctypes.c_double * 2)()
         _check(load_library().taper_kernel_times(self._h, plan._h, _ptr(q), _ptr(kv_pages), _ptr(out), warmup, iters,
                                                  _stream(stream), us))
-        return dict(decode_us=us[0], merge_us=us[1], total_us=us[2])
+        return dict(decode_us=us[0], decode_us_min=us[1])

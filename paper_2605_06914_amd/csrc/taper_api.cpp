@@ -46,8 +46,9 @@ struct PlanBuffers {
 struct taper_ctx {
     taper_attn_config cfg;
     bool host_only = false;
-    void* ws = nullptr;  // partials workspace: [rows] float2 (m, l) then [rows][D] float
+    void* ws = nullptr;  // workspace: [counters] int32 | [rows] float2 (m, l) | [rows][D] float
     int64_t ws_rows = 0;
+    int64_t ws_counters = 0;
     std::vector<PlanBuffers> free_buffers;
 };
 
@@ -104,23 +105,36 @@ int acquire_buffers(taper_ctx* ctx, size_t bytes, PlanBuffers* out) {
     return TAPER_OK;
 }
 
-int ensure_workspace(taper_ctx* ctx, int64_t rows) {
-    if (rows <= ctx->ws_rows) return TAPER_OK;
+size_t ws_ml_offset(const taper_ctx* ctx) { return align_up((size_t)ctx->ws_counters * sizeof(int32_t), 256); }
+size_t ws_o_offset(const taper_ctx* ctx) {
+    return ws_ml_offset(ctx) + align_up((size_t)ctx->ws_rows * sizeof(float2), 256);
+}
+
+// Grows the workspace to hold `rows` partial rows and `counters` arrival counters.
+// Counters are zero whenever no launch is in flight: each launch leaves them so.
+int ensure_workspace(taper_ctx* ctx, int64_t rows, int64_t counters) {
+    if (rows <= ctx->ws_rows && counters <= ctx->ws_counters) return TAPER_OK;
     if (ctx->ws) {
         HIP_TRY(hipDeviceSynchronize());
         HIP_TRY(hipFree(ctx->ws));
         ctx->ws = nullptr;
-        ctx->ws_rows = 0;
+        ctx->ws_rows = ctx->ws_counters = 0;
     }
-    const int64_t want = rows + rows / 4 + 1024;  // head-room so steady-state steps do not reallocate
-    const size_t bytes = align_up((size_t)want * sizeof(float2), 256) + (size_t)want * ctx->cfg.head_dim * sizeof(float);
+    const int64_t want_rows = rows + rows / 4 + 1024;  // head-room so steady-state steps do not reallocate
+    const int64_t want_cnt = counters + counters / 4 + 1024;
+    ctx->ws_rows = want_rows;
+    ctx->ws_counters = want_cnt;
+    const size_t bytes = ws_o_offset(ctx) + (size_t)want_rows * ctx->cfg.head_dim * sizeof(float);
     hipError_t e = hipMalloc(&ctx->ws, bytes);
+    if (e == hipSuccess) e = hipMemset(ctx->ws, 0, ws_ml_offset(ctx));
+    if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
+        if (ctx->ws) (void)hipFree(ctx->ws);
         ctx->ws = nullptr;
-        g_last_error = std::string("workspace hipMalloc: ") + hipGetErrorString(e);
+        ctx->ws_rows = ctx->ws_counters = 0;
+        g_last_error = std::string("workspace allocation: ") + hipGetErrorString(e);
         return TAPER_ENOMEM;
     }
-    ctx->ws_rows = want;
     return TAPER_OK;
 }
 
@@ -140,8 +154,9 @@ taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const vo
     a.prefix_len = plan->d_prefix_len;
     a.n_prefix_pages = plan->d_n_prefix_pages;
     a.ctx_len = plan->d_ctx_len;
-    a.ws_ml = (float2*)ctx->ws;
-    a.ws_o = (float*)((char*)ctx->ws + align_up((size_t)ctx->ws_rows * sizeof(float2), 256));
+    a.counters = (int32_t*)ctx->ws;
+    a.ws_ml = (float2*)((char*)ctx->ws + ws_ml_offset(ctx));
+    a.ws_o = (float*)((char*)ctx->ws + ws_o_offset(ctx));
     a.bt_stride = plan->host.bt_stride;
     a.n_seqs = plan->host.n_seqs;
     a.n_q_heads = ctx->cfg.n_q_heads;
@@ -159,13 +174,13 @@ int check_step(const taper_ctx* ctx, const taper_plan* plan) {
     if (!ctx || !plan) return fail(TAPER_EINVAL, "null ctx or plan");
     if (plan->ctx != ctx) return fail(TAPER_EINVAL, "plan was built on another context");
     if (ctx->host_only || !plan->buf.dev) return fail(TAPER_EHIP, "host-only context: no device work possible");
-    if (plan->host.n_partial_rows > ctx->ws_rows) return fail(TAPER_EINVAL, "workspace smaller than the plan needs");
+    if (plan->host.n_partial_rows > ctx->ws_rows || (int64_t)plan->host.n_seqs * ctx->cfg.n_kv_heads > ctx->ws_counters)
+        return fail(TAPER_EINVAL, "workspace smaller than the plan needs");
     return TAPER_OK;
 }
 
 int enqueue_step(const taper::StepArgs& a, hipStream_t s) {
     HIP_TRY(taper::launch_decode(a, s));
-    HIP_TRY(taper::launch_merge(a, s));
     return TAPER_OK;
 }
 
@@ -290,7 +305,7 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
     plan->d_prefix_len = (const int32_t*)(d + pieces[5].off);
     plan->d_n_prefix_pages = (const int32_t*)(d + pieces[6].off);
     plan->d_ctx_len = (const int32_t*)(d + pieces[7].off);
-    st = ensure_workspace(ctx, h.n_partial_rows);
+    st = ensure_workspace(ctx, h.n_partial_rows, (int64_t)h.n_seqs * ctx->cfg.n_kv_heads);
     if (st != TAPER_OK) {
         std::string keep = g_last_error;
         taper_plan_free(plan);
@@ -428,43 +443,41 @@ int taper_step_latency_probe(taper_ctx* ctx, const taper_plan* plan, int n_layer
 }
 
 int taper_kernel_times(taper_ctx* ctx, const taper_plan* plan, const void* q, const void* kv_pages, void* out,
-                       int warmup, int iters, void* hip_stream, double us[3]) {
+                       int warmup, int iters, void* hip_stream, double us[2]) {
     int st = check_step(ctx, plan);
     if (st != TAPER_OK) return st;
     if (!q || !kv_pages || !out || !us || iters < 1 || warmup < 0) return fail(TAPER_EINVAL, "bad argument");
     hipStream_t s = (hipStream_t)hip_stream;
     const taper::StepArgs a = make_args(ctx, plan, q, kv_pages, out, nullptr);
-    std::vector<hipEvent_t> ev(3 * (size_t)iters, nullptr);
+    std::vector<hipEvent_t> ev(2 * (size_t)iters, nullptr);
     for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
     int rc = TAPER_OK;
     for (int i = 0; i < warmup + iters && rc == TAPER_OK; ++i) {
         const int k = i - warmup;
         hipError_t e = hipSuccess;
-        if (k >= 0) e = hipEventRecord(ev[3 * k], s);
+        if (k >= 0) e = hipEventRecord(ev[2 * k], s);
         if (e == hipSuccess) e = taper::launch_decode(a, s);
-        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[3 * k + 1], s);
-        if (e == hipSuccess) e = taper::launch_merge(a, s);
-        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[3 * k + 2], s);
+        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[2 * k + 1], s);
         if (e != hipSuccess) rc = fail_hip(e, "kernel timing enqueue");
     }
     hipError_t es = hipStreamSynchronize(s);
     if (rc == TAPER_OK && es != hipSuccess) rc = fail_hip(es, "hipStreamSynchronize");
-    double acc[3] = {0, 0, 0};
+    double sum = 0, mn = 1e300;
     if (rc == TAPER_OK) {
-        for (int k = 0; k < iters && rc == TAPER_OK; ++k)
-            for (int j = 0; j < 2; ++j) {
-                float ms = 0.f;
-                if (hipEventElapsedTime(&ms, ev[3 * k + j], ev[3 * k + j + 1]) != hipSuccess) {
-                    rc = fail(TAPER_EHIP, "hipEventElapsedTime");
-                    break;
-                }
-                acc[j] += ms * 1000.0;
+        for (int k = 0; k < iters; ++k) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, ev[2 * k], ev[2 * k + 1]) != hipSuccess) {
+                rc = fail(TAPER_EHIP, "hipEventElapsedTime");
+                break;
             }
+            sum += ms * 1000.0;
+            mn = std::min(mn, ms * 1000.0);
+        }
     }
-    acc[2] = acc[0] + acc[1];
     for (auto& e : ev) (void)hipEventDestroy(e);
     if (rc != TAPER_OK) return rc;
-    for (int j = 0; j < 3; ++j) us[j] = acc[j] / iters;
+    us[0] = sum / iters;
+    us[1] = mn;
     return TAPER_OK;
 }
 

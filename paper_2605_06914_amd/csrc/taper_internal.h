@@ -24,6 +24,7 @@ struct StepArgs {
     const int32_t* ctx_len;
     float2* ws_ml;             // [n_partial_rows] (running max in log2 units, sum)
     float* ws_o;               // [n_partial_rows][D] unnormalised
+    int32_t* counters;         // [n_seqs][n_kv_heads] partials delivered so far; zero between launches
     int32_t bt_stride;
     int32_t n_seqs;
     int32_t n_q_heads, n_kv_heads, gqa, head_dim;
@@ -33,7 +34,6 @@ struct StepArgs {
 };
 
 hipError_t launch_decode(const StepArgs& a, hipStream_t s);
-hipError_t launch_merge(const StepArgs& a, hipStream_t s);
 hipError_t launch_resolve_slots(const StepArgs& a, int64_t* slots, int64_t stride, hipStream_t s);
 
 }  // namespace taper

@@ -16,7 +16,8 @@
 //
 // Softmax state per query row (one lane column): running max m in log2 units
 // (scale*log2(e) folded in), running sum l, unnormalised O.  Partials of the KV
-// chunks of a sequence are combined by merge_kernel through their (m, l).
+// chunks of a sequence are combined through their (m, l) by the workgroup that
+// delivers the sequence's last partial (merge_rows).
 #include "taper_internal.h"
 
 namespace taper {
@@ -31,6 +32,9 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 DEV f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
 DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 DEV bf16x8 cat(bf16x4 a, bf16x4 b) { return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7); }
+// KV is read exactly once per launch: stream it past the caches (measurably faster than cached loads)
+template <typename T>
+DEV T stream_load(const T* p) { return __builtin_nontemporal_load(p); }
 DEV float max4(f32x4 v) { return fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])); }
 
 // Scores of invalid tokens of a chunk's last 32-token block -> -inf.
@@ -74,6 +78,113 @@ DEV float sum_lane_groups(float v) {
     return v;
 }
 
+
+// Partials travel between workgroups inside one launch.  Workgroups may sit on
+// different XCDs, whose L2s are not kept coherent for ordinary cached accesses,
+// and a device-scope fence per workgroup (L2 write-back + invalidate) is far too
+// slow.  So every partial word is written and read with device-scope atomic
+// accesses (write-through stores, cache-bypassing loads, 8 bytes each), and the
+// only ordering needed is "my stores have completed before I count myself in".
+DEV void coherent_store2(float* p, float x, float y) {
+    unsigned long long v = ((unsigned long long)__float_as_uint(y) << 32) | __float_as_uint(x);
+    __hip_atomic_store((unsigned long long*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+DEV float2 coherent_load2(const float* p) {
+    const unsigned long long v = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((unsigned)v), __uint_as_float((unsigned)(v >> 32)));
+}
+DEV void coherent_store4(float* p, f32x4 v) {
+    coherent_store2(p, v[0], v[1]);
+    coherent_store2(p + 2, v[2], v[3]);
+}
+DEV f32x4 coherent_load4(const float* p) {
+    const float2 a = coherent_load2(p), b = coherent_load2(p + 2);
+    f32x4 r = {a.x, a.y, b.x, b.y};
+    return r;
+}
+// all of this thread's earlier stores have completed (no cache maintenance)
+DEV void stores_done() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+
+// Log-sum-exp merge of all partials of (sequence s, kv head hk) -- its request's
+// prefix chunks and its own private chunks -- then normalisation and rounding to
+// bf16.  Threads idx0, idx0+stride, ... each own one float4 of the g x D result;
+// a thread works on U of them at once and takes the entries four at a time, so
+// that 4*U independent loads are in flight per round (the loads bypass the caches
+// and cost a full memory latency each).  Entries are taken in plan order, so the
+// result does not depend on which workgroup happens to run this.
+template <int D, int U>
+DEV void merge_rows(const StepArgs& a, const int s, const int hk, const int idx0, const int stride) {
+    const int g = a.gqa;
+    const int total = g * (D / 4);
+    const int e0 = a.merge_start[s], e1 = a.merge_start[s + 1];
+    for (int base = idx0; base < total; base += stride * U) {
+        float M[U], L[U];
+        f32x4 acc[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            M[u] = -INFINITY;
+            L[u] = 0.f;
+            acc[u] = (f32x4)(0.f);
+        }
+        for (int e = e0; e < e1; e += 4) {
+            float2 ml[U][4];
+            f32x4 o[U][4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const bool have = e + k < e1;
+                const taper_merge_entry me = a.merge[have ? e + k : e];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int idx = base + u * stride;
+                    const bool ok = have && idx < total;
+                    const int j = ok ? idx / (D / 4) : 0, d4 = ok ? idx % (D / 4) : 0;
+                    const int64_t rowi = (int64_t)me.first_row + (int64_t)hk * me.rows_per_head + j;
+                    ml[u][k] = coherent_load2((const float*)(a.ws_ml + rowi));
+                    o[u][k] = coherent_load4(a.ws_o + rowi * D + 4 * d4);
+                    if (!ok) ml[u][k] = make_float2(-INFINITY, 0.f);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float mn = fmaxf(fmaxf(M[u], fmaxf(ml[u][0].x, ml[u][1].x)), fmaxf(ml[u][2].x, ml[u][3].x));
+                const float keep = fast_exp2(M[u] - mn);  // first round: exp2(-inf) = 0
+                L[u] *= keep;
+                acc[u] *= keep;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float w = fast_exp2(ml[u][k].x - mn);
+                    L[u] += w * ml[u][k].y;
+                    acc[u] += w * o[u][k];
+                }
+                M[u] = mn;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int idx = base + u * stride;
+            if (idx < total) {
+                const int j = idx / (D / 4), d4 = idx % (D / 4);
+                const int h = hk * g + j;
+                const f32x4 r = acc[u] * (1.0f / L[u]);
+                *(bf16x4*)((__bf16*)a.out + ((int64_t)s * a.n_q_heads + h) * D + 4 * d4) = __builtin_convertvector(r, bf16x4);
+                if (a.lse && d4 == 0) a.lse[(int64_t)s * a.n_q_heads + h] = (M[u] + __log2f(L[u])) * 0.6931471805599453f;
+            }
+        }
+    }
+}
+
+// A workgroup that has written a partial of (sequence s, kv head hk) announces it.
+// Returns true to the one caller that arrives last: every other partial of that
+// (s, hk) has then been written through (each writer waited for its stores before
+// its increment) and the caller must merge.  The counter is left at zero for the next launch.
+DEV bool arrive_last(const StepArgs& a, const int s, const int hk) {
+    const int n_entries = a.merge_start[s + 1] - a.merge_start[s];
+    int* c = a.counters + (int64_t)s * a.n_kv_heads + hk;
+    const bool last = atomicAdd(c, 1) == n_entries - 1;
+    if (last) *c = 0;
+    return last;
+}
+
 // ---------------------------------------------------------------------------
 // Private / serial kernel: one sequence's g query rows (one 16-row tile, rows
 // >= g idle) against a chunk of that sequence's own pages.  No reuse across
@@ -90,6 +201,7 @@ template <int D>
 struct PrivateSmem {
     float o[4][16][D + 4];
     float2 ml[4][16];
+    int last;
 };
 
 template <int D>
@@ -138,13 +250,13 @@ DEV void private_path(const StepArgs& a, const int part, const int hk, PrivateSm
             const __bf16* vb = kb + (int64_t)Hkv * TILE;
 #pragma unroll
             for (int j = 0; j < KS; ++j) {
-                r.kx[j] = *(const bf16x8*)(ka + koff + j * 512);
-                r.ky[j] = *(const bf16x8*)(kb + koff + j * 512);
+                r.kx[j] = stream_load((const bf16x8*)(ka + koff + j * 512));
+                r.ky[j] = stream_load((const bf16x8*)(kb + koff + j * 512));
             }
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
-                r.va[dt] = *(const bf16x4*)(va + voff + dt * 64);
-                r.vb[dt] = *(const bf16x4*)(vb + voff + dt * 64);
+                r.va[dt] = stream_load((const bf16x4*)(va + voff + dt * 64));
+                r.vb[dt] = stream_load((const bf16x4*)(vb + voff + dt * 64));
             }
         };
         auto compute_block = [&](int b, const KVRegs<D>& r) {
@@ -200,10 +312,15 @@ DEV void private_path(const StepArgs& a, const int part, const int hk, PrivateSm
                 acc += wg * *(const f32x4*)&sm_o[w][r][4 * d4];
             }
             const int64_t slot = (int64_t)item.part_base + hk * g + r;
-            *(f32x4*)(a.ws_o + slot * D + 4 * d4) = acc;
-            if (d4 == 0) a.ws_ml[slot] = make_float2(M, L);
+            coherent_store4(a.ws_o + slot * D + 4 * d4, acc);
+            if (d4 == 0) coherent_store2((float*)(a.ws_ml + slot), M, L);
         }
+        // publish the partial; whoever completes the sequence's set merges it
+        stores_done();
         __syncthreads();
+        if (threadIdx.x == 0) sm.last = arrive_last(a, item.seq0, hk);
+        __syncthreads();
+        if (sm.last) merge_rows<D, 1>(a, item.seq0, hk, threadIdx.x, 256);
     }
 }
 
@@ -221,6 +338,7 @@ struct SharedSmem {
     static constexpr int PAGE_LDS = TILE + 4 * VQ;
     static constexpr int BUF = 4 * PAGE_LDS;  // 4 pages = 64 tokens
     __bf16 kv[2 * BUF];
+    int last[64];  // per branch of the current item
 };
 
 template <int D, int NTW>
@@ -276,22 +394,23 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
             for (int dt = 0; dt < DT; ++dt) O[k][dt] = (f32x4)(0.f);
         }
 
-        bf16x8 stg[8];
-        auto stage_load = [&](int b) {
-            if (stager) {
+        // Two register sets: while block b is computed from LDS, blocks b+1 and b+2 are in flight.
+        bf16x8 stgA[8], stgB[8];
+        auto stage_load = [&](int b, bf16x8 (&stg)[8]) {
+            if (stager && b < n_blocks) {
 #pragma unroll
                 for (int pg = 0; pg < 4; ++pg) {
                     const int ip = 4 * b + pg < n_pages ? 4 * b + pg : n_pages - 1;
                     const int64_t pid = row[ip];
                     const __bf16* kp = kvb + pid * page_elems + (int64_t)hk * TILE + se;
-                    stg[2 * pg] = *(const bf16x8*)kp;
-                    stg[2 * pg + 1] = *(const bf16x8*)(kp + (int64_t)Hkv * TILE);
+                    stg[2 * pg] = stream_load((const bf16x8*)kp);
+                    stg[2 * pg + 1] = stream_load((const bf16x8*)(kp + (int64_t)Hkv * TILE));
                 }
             }
         };
-        auto stage_store = [&](int buf) {
-            if (stager) {
-                __bf16* base = lds + buf * BUF;
+        auto stage_store = [&](int b, const bf16x8 (&stg)[8]) {
+            if (stager && b < n_blocks) {
+                __bf16* base = lds + (b & 1) * BUF;
 #pragma unroll
                 for (int pg = 0; pg < 4; ++pg) {
                     *(bf16x8*)(base + pg * PAGE_LDS + se) = stg[2 * pg];
@@ -337,14 +456,19 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
             }
         };
 
-        stage_load(0);
-        stage_store(0);
+        stage_load(0, stgA);
+        stage_load(1, stgB);
+        stage_store(0, stgA);
         __syncthreads();
-        for (int b = 0; b < n_blocks; ++b) {
-            const bool more = b + 1 < n_blocks;
-            if (more) stage_load(b + 1);
+        for (int b = 0; b < n_blocks; b += 2) {
+            stage_load(b + 2, stgA);
             compute(b, b & 1);
-            if (more) stage_store((b + 1) & 1);
+            stage_store(b + 1, stgB);
+            __syncthreads();
+            if (b + 1 >= n_blocks) break;
+            stage_load(b + 3, stgB);
+            compute(b + 1, (b + 1) & 1);
+            stage_store(b + 2, stgA);
             __syncthreads();
         }
 
@@ -355,12 +479,20 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
                 const int r = 16 * (wave + 4 * k) + n;
                 if (r < R) {
                     const int64_t slot = (int64_t)item.part_base + (int64_t)hk * R + r;
-                    if (qd == 0) a.ws_ml[slot] = make_float2(m[k], lt);
+                    if (qd == 0) coherent_store2((float*)(a.ws_ml + slot), m[k], lt);
 #pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) *(f32x4*)(a.ws_o + slot * D + 16 * dt + 4 * qd) = O[k][dt];
+                    for (int dt = 0; dt < DT; ++dt) coherent_store4(a.ws_o + slot * D + 16 * dt + 4 * qd, O[k][dt]);
                 }
             }
         }
+        // publish the partials; for every branch whose set is now complete, merge (one wave per branch)
+        stores_done();
+        __syncthreads();
+        if (tid < item.n_branch) sm.last[tid] = arrive_last(a, item.seq0 + tid, hk);
+        __syncthreads();
+        for (int b = wave; b < item.n_branch; b += 4)
+            if (sm.last[b]) merge_rows<D, 2>(a, item.seq0 + b, hk, lane, 64);
+        __syncthreads();
     }
 }
 
@@ -377,44 +509,21 @@ __global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void decode_kernel(StepArg
     __shared__ __attribute__((aligned(16))) char smem_raw[sizeof(Smem)];
     const int part = blockIdx.x / a.n_kv_heads;
     const int hk = blockIdx.x % a.n_kv_heads;
+#ifdef TAPER_WG_TRACE  // development builds only: per-workgroup start/end clock into the lse buffer
+    StepArgs b = a;
+    b.lse = nullptr;
+    if (threadIdx.x == 0) ((long long*)a.lse)[2 * blockIdx.x] = wall_clock64();
+    if (part < a.n_parts_shared)
+        shared_path<D, NTW>(b, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
+    else
+        private_path<D>(b, part, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
+    if (threadIdx.x == 0) ((long long*)a.lse)[2 * blockIdx.x + 1] = wall_clock64();
+#else
     if (part < a.n_parts_shared)
         shared_path<D, NTW>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
     else
         private_path<D>(a, part, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
-}
-
-// ---------------------------------------------------------------------------
-// Log-sum-exp merge of a sequence's partials (its request's prefix chunks and
-// its own private chunks), normalisation and rounding to bf16.
-// ---------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256) void merge_kernel(StepArgs a) {
-    const int s = blockIdx.x;
-    const int idx = blockIdx.y * 256 + threadIdx.x;
-    if (idx >= a.n_q_heads * (D / 4)) return;
-    const int h = idx / (D / 4), d4 = idx % (D / 4);
-    const int hk = h / a.gqa, j = h % a.gqa;
-    const int e0 = a.merge_start[s], e1 = a.merge_start[s + 1];
-    float M = -INFINITY;
-    for (int e = e0; e < e1; ++e) {
-        const taper_merge_entry me = a.merge[e];
-        M = fmaxf(M, a.ws_ml[(int64_t)me.first_row + (int64_t)hk * me.rows_per_head + j].x);
-    }
-    float L = 0.f;
-    f32x4 acc = (f32x4)(0.f);
-    for (int e = e0; e < e1; ++e) {
-        const taper_merge_entry me = a.merge[e];
-        const int64_t rowi = (int64_t)me.first_row + (int64_t)hk * me.rows_per_head + j;
-        const float2 ml = a.ws_ml[rowi];
-        const float w = fast_exp2(ml.x - M);
-        L += w * ml.y;
-        acc += w * *(const f32x4*)(a.ws_o + rowi * D + 4 * d4);
-    }
-    const float inv = 1.0f / L;
-    acc *= inv;
-    const bf16x4 o = __builtin_convertvector(acc, bf16x4);
-    *(bf16x4*)((__bf16*)a.out + ((int64_t)s * a.n_q_heads + h) * D + 4 * d4) = o;
-    if (a.lse && d4 == 0) a.lse[(int64_t)s * a.n_q_heads + h] = (M + __log2f(L)) * 0.6931471805599453f;
+#endif
 }
 
 // Physical slot of every logical position, from the device copy of the plan.
@@ -455,15 +564,6 @@ hipError_t launch_decode(const StepArgs& a, hipStream_t s) {
     } else {
         return hipErrorInvalidValue;
     }
-    return hipGetLastError();
-}
-
-hipError_t launch_merge(const StepArgs& a, hipStream_t s) {
-    const int per_seq = a.n_q_heads * (a.head_dim / 4);
-    const dim3 grid(a.n_seqs, (per_seq + 255) / 256), block(256);
-    if (a.head_dim == 128) hipLaunchKernelGGL((merge_kernel<128>), grid, block, 0, s, a);
-    else if (a.head_dim == 64) hipLaunchKernelGGL((merge_kernel<64>), grid, block, 0, s, a);
-    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

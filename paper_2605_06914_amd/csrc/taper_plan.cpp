@@ -118,7 +118,7 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
     int target_wgs = opts && opts->target_workgroups > 0 ? opts->target_workgroups : 512;
     const bool share_prefix = opts ? opts->share_prefix != 0 : true;
     int max_tiles = kMaxRowTilesPerItem;
-    int cap_branches = std::max(2, max_tiles * 16 / g);
+    int cap_branches = std::min(64, std::max(2, max_tiles * 16 / g));  // 64: per-branch flags of the shared kernel
     if (opts && opts->max_branches_per_item > 0) cap_branches = std::max(1, std::min(cap_branches, opts->max_branches_per_item));
 
     HostPlan& p = *out;
@@ -224,19 +224,24 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
         }
     }
 
-    // ---- workgroup shares: both kinds run in one launch, so every share gets about the same
-    // number of tokens: total tokens / (target_wgs / Hkv), rounded up to whole 64-token blocks
-    int64_t tok_total = 0;
-    for (const Segment& s : shared) tok_total += s.n_tokens;
-    for (const Segment& s : priv) tok_total += s.n_tokens;
+    // ---- workgroup shares: both kinds run in one launch and should finish together.  A workgroup of
+    // the shared kind keeps fewer bytes in flight than one of the private kind and so gets a smaller
+    // slice of a saturated memory system: its tokens are weighted by shared_cost_pct / 100.
+    const int64_t w_pct = opts && opts->shared_cost_pct > 0 ? opts->shared_cost_pct : 130;
+    int64_t tok_shared = 0, tok_priv = 0;
+    for (const Segment& s : shared) tok_shared += s.n_tokens;
+    for (const Segment& s : priv) tok_priv += s.n_tokens;
+    const int64_t tok_total = tok_shared + tok_priv;
     const int parts_total = std::max(1, target_wgs / cfg.n_kv_heads);
-    int64_t quota_tokens = (tok_total + parts_total - 1) / parts_total;
+    // quota of the private kind in tokens; the shared kind gets quota * 100 / w_pct
+    int64_t quota_tokens = ((tok_shared * w_pct + 99) / 100 + tok_priv + parts_total - 1) / parts_total;
     quota_tokens = std::max<int64_t>(kSharedBlockTokens, (quota_tokens + kSharedBlockTokens - 1) / kSharedBlockTokens * kSharedBlockTokens);
     for (;;) {  // never more shares than asked for: an extra one would run after all the others
         p.items.clear();
-        p.n_parts_shared = partition(shared, quota_tokens / kSharedBlockTokens, kSharedBlockTokens, 0, &p.items);
+        const int64_t quota_shared = std::max<int64_t>(1, quota_tokens * 100 / w_pct / kSharedBlockTokens);
+        p.n_parts_shared = partition(shared, quota_shared, kSharedBlockTokens, 0, &p.items);
         p.n_parts_private = partition(priv, quota_tokens / kPrivateBlockTokens, kPrivateBlockTokens, p.n_parts_shared, &p.items);
-        if (p.n_parts_shared + p.n_parts_private <= parts_total || quota_tokens >= tok_total) break;
+        if (p.n_parts_shared + p.n_parts_private <= parts_total || quota_tokens >= tok_total * 2) break;
         quota_tokens += kSharedBlockTokens;
     }
     const int n_parts = p.n_parts_shared + p.n_parts_private;

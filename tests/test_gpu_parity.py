@@ -243,7 +243,7 @@ def test_step_latency_probe_runs(ctx_qwen):
     for o in outs:
         assert_parity(f32_from_bf16_bits(bits_from_torch(o)).astype(np.float64), ref, "probe layer")
     kt = ctx_qwen.kernel_times(plan, q, kv, outs[0], warmup=1, iters=3)
-    assert kt["decode_us"] > 0 and kt["merge_us"] > 0
+    assert kt["decode_us"] >= kt["decode_us_min"] > 0
     plan.free()
 
 
