@@ -30,13 +30,16 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="mixed", choices=["mixed", "irp_off", "long", "tiny"])
+    ap.add_argument("--workload", default="mixed", choices=["mixed", "irp_off", "long", "tiny", "sweep"])
     ap.add_argument("--layers", type=int, default=0, help="layers per step (0 = workload default)")
     ap.add_argument("--target-workgroups", type=int, default=0)
     ap.add_argument("--shared-cost-pct", type=int, default=0)
     ap.add_argument("--no-share", action="store_true", help="every branch streams its prefix itself (for comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=20)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy 5 times: scales the FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--sweep-pools", type=int, default=16, help="distinct KV pools the 64 layers of the sweep cycle through")
     return ap.parse_args()
 
 
@@ -45,6 +48,69 @@ def make_structure(name):
 
     return {"tiny": structure_config1, "irp_off": structure_config2, "mixed": structure_config3,
             "long": structure_config4}[name]()
+
+
+def run_sweep(args):
+    """Admission sweep (paper §2.3: branch externality E(k) = T(S(k)) - T(S_0)): 96 serial + 32 parallel
+    requests on a 64-layer stack; every parallel request runs its protected branch plus k opportunistic
+    ones, k in {0,2,4,8,16}.  64 independent pools of this size do not fit one GPU (k=16: 64 x 5.6 GB), so
+    layer l reads pool l mod --sweep-pools; each layer's working set (3-5 GB) is far beyond the 256 MB
+    Infinity Cache, so reuse of a pool 16 layers later cannot hit in cache."""
+    import torch
+
+    from paper_2605_06914_amd import Context
+    from taper_inputs import structure_config5
+
+    dev = torch.device("cuda:0")
+    n_layers = args.layers or 64
+    sts = {k: structure_config5(k) for k in (0, 2, 4, 8, 16)}
+    sh = sts[0].shape
+    n_pool_pages = sts[16].n_pool_pages
+    assert all(st.n_pool_pages == n_pool_pages for st in sts.values())
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(sts[0].seed + 1000)
+    pool_elems = n_pool_pages * sh.page_elems
+    pools = []
+    for _ in range(args.sweep_pools):
+        kv = torch.empty(pool_elems, device=dev, dtype=torch.bfloat16)
+        chunk = 1 << 28
+        for o in range(0, pool_elems, chunk):
+            n = min(chunk, pool_elems - o)
+            kv[o : o + n] = torch.randn(n, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        pools.append(kv)
+    s_max = sts[16].n_seqs
+    qs = [torch.randn((s_max, sh.n_q_heads, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16)
+          for _ in range(n_layers)]
+    outs = [torch.zeros((s_max, sh.n_q_heads, sh.head_dim), device=dev, dtype=torch.bfloat16) for _ in range(n_layers)]
+    kvs = [pools[l % args.sweep_pools] for l in range(n_layers)]
+    torch.cuda.synchronize()
+    ctx = Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, device=0)
+    rows = []
+    for k, st in sts.items():
+        def step():
+            plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages,
+                                  target_workgroups=args.target_workgroups, shared_cost_pct=args.shared_cost_pct)
+            for l in range(n_layers):
+                ctx.decode_step_attention(plan, qs[l], kvs[l], outs[l])
+            plan.free()
+
+        for _ in range(max(1, args.warmup)):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / args.steps * 1e3
+        gbps = (st.kv_bytes_unique + st.qo_bytes) * n_layers / (ms * 1e-3) / 1e9
+        rows.append({"k": k, "admitted_branches": 32 * k, "n_seqs": st.n_seqs, "l_context": st.logical_tokens,
+                     "tokens_unique": st.unique_tokens, "ms_per_step": round(ms, 3), "gbps_unique": round(gbps, 1),
+                     "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)})
+    t_base = rows[0]["ms_per_step"]
+    for r in rows:
+        r["externality_ms"] = round(r["ms_per_step"] - t_base, 3)
+    ctx.close()
+    return rows, n_layers, sh
 
 
 def main():
@@ -60,6 +126,26 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB read, 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}}))
+        return
+    if args.workload == "sweep":
+        rows, n_layers, sh = run_sweep(args)
+        top = rows[-1]
+        print(json.dumps({
+            "metric": "decode_step_attention_effective_kv_bandwidth", "value": top["gbps_unique"], "unit": "GB/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": top["ms_per_step"],
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"config5 admission sweep x {n_layers} layers, value quoted at k=16 "
+                                   f"({args.sweep_pools} distinct KV pools cycled over the layers)",
+                       "n_layers": n_layers},
+            "step_latency_vs_admitted_branches": rows}))
+        return
     st = make_structure(args.workload)
     sh = st.shape
     # default depth: the 64-layer stack of the model the shape comes from; the long workload's pool is

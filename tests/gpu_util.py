@@ -57,3 +57,46 @@ def assert_parity(got, ref, what=""):
     # output alone is 2^-9 relative per element, so hold the error to a few percent of the output scale too
     assert mx <= 0.05 * rms + 1e-6, f"{what}: max-abs {mx} is more than 5% of rms(ref) {rms}"
     return mx, mean
+
+
+def device_random_batch(st, seed=None, device="cuda:0"):
+    """q and the whole pool drawn on the device (N(0,1) rounded to bf16); for pools too big for numpy."""
+    import torch
+
+    sh = st.shape
+    gen = torch.Generator(device=device)
+    gen.manual_seed((st.seed + 1000) if seed is None else seed)
+    q = torch.randn((st.n_seqs, sh.n_q_heads, sh.head_dim), generator=gen, device=device).to(torch.bfloat16)
+    n = st.n_pool_pages * sh.page_elems
+    kv = torch.empty(n, device=device, dtype=torch.bfloat16)
+    chunk = 1 << 28
+    for o in range(0, n, chunk):
+        m = min(chunk, n - o)
+        kv[o : o + m] = torch.randn(m, generator=gen, device=device).to(torch.bfloat16)
+    return q, kv
+
+
+def host_subbatch(st, q_dev, kv_dev, rows):
+    """The sequences `rows` with just the pages they reference, copied to the host."""
+    import torch
+
+    from taper_inputs import compact_rows
+
+    rows = np.asarray(sorted(rows))
+    sub, pages = compact_rows(st, rows)
+    sh = st.shape
+    pg = torch.from_numpy(pages).to(kv_dev.device)
+    kv = bits_from_torch(kv_dev.view(st.n_pool_pages, sh.page_elems)[pg])
+    q = bits_from_torch(q_dev[torch.from_numpy(rows).to(q_dev.device)])
+    return rows, Batch(sub, q, kv)
+
+
+def run_gpu_device(ctx, st, q_dev, kv_dev, **plan_kw):
+    import torch
+
+    out = torch.full_like(q_dev, float("nan"))
+    plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages, **plan_kw)
+    ctx.decode_step_attention(plan, q_dev, kv_dev, out)
+    torch.cuda.synchronize()
+    plan.free()
+    return out

@@ -270,3 +270,56 @@ def test_config3_full_size_sampled(ctx_qwen):
     sub, pages = compact_rows(st, rows)
     ref, _ = run_oracle(Batch(sub, b.q[rows], b.kv[pages]))
     assert_parity(got[rows], ref, "config3 sampled")
+
+
+def sample_rows(st, n_serial=8):
+    sizes = np.bincount(st.branch_group)
+    serial = [s for s in range(st.n_seqs) if sizes[st.branch_group[s]] == 1]
+    rows = serial[:: max(1, len(serial) // n_serial)][:n_serial]
+    for g in np.flatnonzero(sizes > 1):
+        m = np.flatnonzero(st.branch_group == g)
+        rows += [int(m[0]), int(m[-1])]
+    return sorted(set(rows))
+
+
+def test_config4_long_context_sampled(ctx_qwen):
+    """Long-context batch at full size: 8 requests with a 32768-token prefix and 16 branches plus 32 serial
+    requests, pages scattered in a ~30 GB pool (64-bit addressing, 458k pages).  The oracle checks 8 serial
+    sequences and every request's first and last branch, all heads; all outputs must be finite."""
+    import torch
+
+    from taper_inputs import structure_config4
+    from tests.gpu_util import device_random_batch, host_subbatch, run_gpu_device
+
+    st = structure_config4()
+    assert st.n_pool_pages * st.shape.page_elems * 2 > 29e9
+    q, kv = device_random_batch(st)
+    out = run_gpu_device(ctx_qwen, st, q, kv)
+    assert bool(torch.isfinite(out.float()).all())
+    rows, sub = host_subbatch(st, q, kv, sample_rows(st))
+    del kv
+    torch.cuda.empty_cache()
+    ref, _ = run_oracle(sub)
+    got = f32_from_bf16_bits(bits_from_torch(out[torch.from_numpy(rows).to(out.device)])).astype(np.float64)
+    assert_parity(got, ref, "config4 sampled")
+
+
+@pytest.mark.parametrize("k", [0, 4, 16])
+def test_config5_sweep_point_sampled(ctx_qwen, k):
+    """One layer of the admission sweep at full size (96 serial + 32 parallel requests, width 1+k)."""
+    import torch
+
+    from taper_inputs import structure_config5
+    from tests.gpu_util import device_random_batch, host_subbatch, run_gpu_device
+
+    st = structure_config5(k)
+    assert st.n_seqs == 96 + 32 * (1 + k)
+    q, kv = device_random_batch(st)
+    out = run_gpu_device(ctx_qwen, st, q, kv)
+    assert bool(torch.isfinite(out.float()).all())
+    rows, sub = host_subbatch(st, q, kv, sample_rows(st, n_serial=6)[:40])
+    del kv
+    torch.cuda.empty_cache()
+    ref, _ = run_oracle(sub)
+    got = f32_from_bf16_bits(bits_from_torch(out[torch.from_numpy(rows).to(out.device)])).astype(np.float64)
+    assert_parity(got, ref, f"config5 k={k} sampled")
