@@ -789,6 +789,476 @@ __global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void decode_kernel(StepArg
     }
 }
 
+// ---------------------------------------------------------------------------
+// Queues that hold private units only: three waves of a workgroup stream, the
+// fourth is the workgroup's control wave.  Everything with a long latency that
+// is not KV streaming (claims from the queue, combining the streaming waves'
+// states, storing partial rows and waiting for the stores, arrival atomics,
+// merges) is the control wave's business, so the streaming waves never wait for
+// anything but their own KV loads.  The waves talk through LDS only:
+//   ring[k % RING]   unit number k of this workgroup, published by the control wave
+//   blk[k % RING]    next unclaimed 32-token block of unit k (streaming waves take blocks as they go)
+//   done[k % RING]   streaming waves that have left unit k and dumped their state
+//   consumed         units whose states the control wave has combined (their state slots are free)
+// No workgroup barrier is used.  Every wait is a bounded spin on an LDS word that
+// another wave is certain to write; if a spin ever ran out, the wave raises the
+// error word and leaves.
+// ---------------------------------------------------------------------------
+constexpr int RING = 4;
+constexpr int STREAM_WAVES = 3;
+constexpr int SPIN_LIMIT = 1 << 22;  // x s_sleep(1) of 64 clocks: seconds, far beyond any legitimate wait
+
+struct RingUnit {
+    long long row_off;  // elements from the block table's base to the unit's first entry
+    int seq0, n_tok, part_base, kind;
+};
+
+template <int D>
+struct SpecSmem {
+    float o[2][STREAM_WAVES][16][D + 4];
+    float2 ml[2][STREAM_WAVES][16];
+    RingUnit ring[RING];
+    int blk[RING];
+    int done[RING];
+    int published;  // units (and the end marker) published so far
+    int consumed;
+    int failed;
+};
+
+DEV int lds_load_acquire(const int* p) { return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP); }
+DEV void lds_store_release(int* p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP); }
+
+// Spins until *p >= want (or the workgroup has failed).  Returns false on failure.
+DEV bool spin_until_at_least(const StepArgs& a, int* failed, const int* p, const int want) {
+    for (int i = 0; i < SPIN_LIMIT; ++i) {
+        if (lds_load_acquire(p) >= want) return true;
+        if (lds_load_acquire(failed)) return false;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    lds_store_release(failed, 1);
+    a.queue[a.n_kv_heads + 1] = 1;  // error word, checked by the host after synchronising
+    return false;
+}
+
+template <int D>
+DEV void stream_wave(const StepArgs& a, const int hk, SpecSmem<D>& sm, const int wave) {
+    constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D;
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15, qd = lane >> 4;
+    const int Hkv = a.n_kv_heads, g = a.gqa;
+    const __bf16* __restrict__ kvb = (const __bf16*)a.kv;
+    const int64_t page_elems = 2LL * Hkv * TILE;
+    const float c = a.scale_log2e;
+    const int koff = lane * 8, voff = qd * (4 * D) + n * 4;
+
+    auto read_ring = [&](const int k, RingUnit& u) INLINE_LAMBDA {
+        const RingUnit& r = sm.ring[k % RING];
+        u.row_off = ((long long)__builtin_amdgcn_readfirstlane((int)(r.row_off >> 32)) << 32) |
+                    (unsigned)__builtin_amdgcn_readfirstlane((int)r.row_off);
+        u.seq0 = __builtin_amdgcn_readfirstlane(r.seq0);
+        u.n_tok = __builtin_amdgcn_readfirstlane(r.n_tok);
+        u.part_base = __builtin_amdgcn_readfirstlane(r.part_base);
+        u.kind = __builtin_amdgcn_readfirstlane(r.kind);
+    };
+    bf16x8 qf[KS], qn[KS];  // q of the unit being computed / of the unit the loads have run ahead into
+    auto load_q = [&](const RingUnit& un, bf16x8 (&q)[KS]) INLINE_LAMBDA {
+        const __bf16* qrow = (const __bf16*)a.q + ((int64_t)un.seq0 * a.n_q_heads + hk * g + (n < g ? n : 0)) * D;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            bf16x8 v = *(const bf16x8*)(qrow + 8 * (4 * j + qd));
+            if (n >= g) v = (bf16x8)(0);
+            q[j] = v;
+        }
+    };
+    float m = -INFINITY, l = 0.f;
+    f32x4 O[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) O[dt] = (f32x4)(0.f);
+
+    int kC = 0, kL = 0;  // this wave computes unit kC; it claims blocks of unit kL (kC or kC + 1)
+    RingUnit uC, uL;
+    if (!spin_until_at_least(a, &sm.failed, &sm.published, 1)) return;
+    read_ring(0, uC);
+    if (uC.kind != 1) return;
+    uL = uC;
+    load_q(uC, qf);
+#pragma unroll
+    for (int j = 0; j < KS; ++j) qn[j] = qf[j];
+
+    // The block this wave loads next is claimed one step before its loads are issued, together
+    // with its page ids, so neither the LDS round trip nor the block-table fetch delays the loads.
+    int nu = -1, nb = 0;       // claimed block: unit number (< 0: none) and block index
+    int64_t npa = 0, npb = 0;  // its pages
+    auto claim = [&]() INLINE_LAMBDA {
+        for (;;) {
+            int got = 0;
+            if (lane == 0) got = __hip_atomic_fetch_add(&sm.blk[kL % RING], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const int b = __builtin_amdgcn_readfirstlane(got);
+            if (32 * b < uL.n_tok) {
+                const int32_t* row = a.bt + uL.row_off;
+                const int n_pages = (uL.n_tok + 15) >> 4;
+                npa = row[2 * b];
+                npb = row[2 * b + 1 < n_pages ? 2 * b + 1 : 2 * b];
+                nu = kL;
+                nb = b;
+                return;
+            }
+            // unit kL has no block left: run ahead into the next unit if it is there, one unit at most
+            if (kL > kC || lds_load_acquire(&sm.published) <= kL + 1) return;
+            RingUnit nx;
+            read_ring(kL + 1, nx);
+            if (nx.kind != 1) return;
+            ++kL;
+            uL = nx;
+            load_q(uL, qn);  // long before the first block of that unit is computed
+        }
+    };
+    auto issue = [&](KVRegs<D>& r) INLINE_LAMBDA {
+        const __bf16* ka = kvb + npa * page_elems + (int64_t)hk * TILE;
+        const __bf16* kb = kvb + npb * page_elems + (int64_t)hk * TILE;
+        const __bf16* va = ka + (int64_t)Hkv * TILE;
+        const __bf16* vb = kb + (int64_t)Hkv * TILE;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            r.kx[j] = stream_load((const bf16x8*)(ka + koff + j * 512));
+            r.ky[j] = stream_load((const bf16x8*)(kb + koff + j * 512));
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            r.va[dt] = stream_load((const bf16x4*)(va + voff + dt * 64));
+            r.vb[dt] = stream_load((const bf16x4*)(vb + voff + dt * 64));
+        }
+    };
+    // Leaves unit kC: this wave's state goes to the unit's LDS slot for the control wave to combine.
+    auto leave_unit = [&]() INLINE_LAMBDA -> bool {
+        if (!spin_until_at_least(a, &sm.failed, &sm.consumed, kC - 1)) return false;  // slot of unit kC-2 is free
+        const int par = kC & 1;
+        l = sum_lane_groups(l);
+        if (n < g) {
+            if (qd == 0) sm.ml[par][wave][n] = make_float2(m, l);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) *(f32x4*)&sm.o[par][wave][n][16 * dt + 4 * qd] = O[dt];
+        }
+        if (lane == 0) __hip_atomic_fetch_add(&sm.done[kC % RING], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        m = -INFINITY;
+        l = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) O[dt] = (f32x4)(0.f);
+        ++kC;
+        return true;
+    };
+    auto compute = [&](const KVRegs<D>& r, const int b) INLINE_LAMBDA {
+        f32x4 sx = (f32x4)(0.f), sy = (f32x4)(0.f);
+#pragma unroll
+        for (int j = 0; j < KS; ++j) {
+            sx = mfma16(r.kx[j], qf[j], sx);
+            sy = mfma16(r.ky[j], qf[j], sy);
+        }
+        const int nv = uC.n_tok - 32 * b;
+        if (nv < 32) mask_tail(sx, sy, qd, nv);
+        const bf16x8 pf = softmax_block<DT>(sx, sy, c, m, l, O);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) O[dt] = mfma16(cat(r.va[dt], r.vb[dt]), pf, O[dt]);
+    };
+
+    // (uX, bX): unit number and block held by register set X, uX < 0 when it holds none
+    int u0 = -1, b0 = 0, u1 = -1, b1 = 0;
+    KVRegs<D> r0, r1;
+    // One step: start the loads of the claimed block into `other` if that set is empty, claim the
+    // block after it, then compute `cur` if it holds a block.
+    // Returns 0 to go on, 1 when neither set holds a block, -1 on failure.
+    auto step = [&](KVRegs<D>& cur, int& uc, const int bc, KVRegs<D>& other, int& uo, int& bo) INLINE_LAMBDA -> int {
+        if (uo < 0) {
+            if (nu < 0) claim();
+            if (nu >= 0) {
+                issue(other);
+                uo = nu;
+                bo = nb;
+                nu = -1;
+#ifndef NO_PRECLAIM
+                claim();
+#endif
+            }
+        }
+        if (uc >= 0) {
+            if (uc != kC) {  // the block belongs to the next unit (kL == kC + 1, its q is in qn)
+                if (!leave_unit()) return -1;
+                uC = uL;
+#pragma unroll
+                for (int j = 0; j < KS; ++j) qf[j] = qn[j];
+            }
+            compute(cur, bc);
+            uc = -1;
+            return 0;
+        }
+        return uo < 0 ? 1 : 0;
+    };
+    for (;;) {
+        int st = step(r0, u0, b0, r1, u1, b1);
+        if (st == 0) st = step(r1, u1, b1, r0, u0, b0);
+        if (st < 0) return;
+        if (st == 0) continue;
+        // Neither set holds a block and none could be claimed: unit kC has none left for this
+        // wave, and the wave could not run ahead (next unit not published yet, not private, or
+        // itself without a block left).
+        if (!leave_unit()) return;
+        if (kL < kC) {
+            if (!spin_until_at_least(a, &sm.failed, &sm.published, kC + 1)) return;
+            read_ring(kC, uL);
+            kL = kC;
+            if (uL.kind != 1) return;
+            load_q(uL, qn);
+        }
+        uC = uL;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) qf[j] = qn[j];
+    }
+}
+
+// The control wave of a workgroup.  In order of priority it (1) publishes the next unit when
+// the streaming waves are about to run out of blocks (claiming it from the queue only then, so
+// a workgroup never sits on unstarted work when the queue runs dry), (2) combines the states of
+// a unit all streaming waves have left and stores its partial rows, (3) advances a merge by one
+// round of entries.  A unit's arrival is announced when the next unit is combined (its stores
+// have completed by then) and the atomic's result is looked at later still, so the wave never
+// waits for an operation it has just issued, except for the claim.
+template <int D>
+DEV void control_wave(const StepArgs& a, const int hk, SpecSmem<D>& sm, const int w) {
+    constexpr int PUBLISH_AHEAD_BLOCKS = 16;  // publish the next unit when so few blocks of the last one are unclaimed
+    const int lane = threadIdx.x & 63;
+    const int g = a.gqa;
+    const int W = a.wgs_per_head;
+    const int total = g * (D / 4);  // float4 pieces of one (sequence, kv head) result; each lane owns up to 4 of them
+    int n_pub = 0, n_cons = 0, n_units = 0;  // ring entries published, units combined, units among the published entries
+    bool end_published = false;
+    int seq0_of[RING], base_of[RING], ntok_of[RING];  // of the units published and not yet combined
+#pragma unroll
+    for (int i = 0; i < RING; ++i) seq0_of[i] = base_of[i] = ntok_of[i] = 0;
+    int seq_stored = -1;              // sequence whose partial rows were stored at the last combine
+    int seq_announced = -1, old = 0;  // sequence whose arrival has been announced; lane 0: the counter before
+    // merge in progress: sequence, next entry, end entry, and the running state of this lane's pieces
+    int mg_seq = -1, mg_e = 0, mg_e1 = 0;
+    float mg_M[4], mg_L[4];
+    f32x4 mg_acc[4];
+    auto merge_round = [&]() INLINE_LAMBDA {  // two entries of the merge in progress
+        taper_merge_entry me[2];
+        bool have[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            have[k] = mg_e + k < mg_e1;
+            me[k] = a.merge[have[k] ? mg_e + k : mg_e];
+        }
+        float2 ml[4][2];
+        f32x4 o[4][2];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = lane + 64 * u;
+            const bool in = idx < total;
+            const int j = in ? idx / (D / 4) : 0, d4 = in ? idx % (D / 4) : 0;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int64_t rowi = (int64_t)me[k].first_row + (int64_t)hk * me[k].rows_per_head + j;
+                ml[u][k] = coherent_load2((const float*)(a.ws_ml + rowi));
+                o[u][k] = coherent_load4(a.ws_o + rowi * D + 4 * d4);
+                if (!have[k] || !in) ml[u][k] = make_float2(-INFINITY, 0.f);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float mn = fmaxf(mg_M[u], fmaxf(ml[u][0].x, ml[u][1].x));
+            const float keep = mg_M[u] == -INFINITY ? 0.f : fast_exp2(mg_M[u] - mn);
+            mg_L[u] *= keep;
+            mg_acc[u] *= keep;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const float wk = ml[u][k].x == -INFINITY ? 0.f : fast_exp2(ml[u][k].x - mn);
+                mg_L[u] += wk * ml[u][k].y;
+                mg_acc[u] += wk * o[u][k];
+            }
+            mg_M[u] = mn;
+        }
+        mg_e += 2;
+        if (mg_e >= mg_e1) {  // normalise, round, write
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = lane + 64 * u;
+                if (idx < total) {
+                    const int j = idx / (D / 4), d4 = idx % (D / 4);
+                    const int h = hk * g + j;
+                    const f32x4 r = mg_acc[u] * (1.0f / mg_L[u]);
+                    *(bf16x4*)((__bf16*)a.out + ((int64_t)mg_seq * a.n_q_heads + h) * D + 4 * d4) = __builtin_convertvector(r, bf16x4);
+                    if (a.lse && d4 == 0) a.lse[(int64_t)mg_seq * a.n_q_heads + h] = (mg_M[u] + __log2f(mg_L[u])) * 0.6931471805599453f;
+                }
+            }
+            mg_seq = -1;
+        }
+    };
+    auto settle = [&]() INLINE_LAMBDA {  // looks at the announced arrival's result; may start a merge
+        const int s = seq_announced;
+        const int e0 = a.merge_start[s], e1 = a.merge_start[s + 1];
+        if (__builtin_amdgcn_readfirstlane(old) == e1 - e0 - 1) {
+            if (lane == 0) a.counters[(int64_t)s * a.n_kv_heads + hk] = 0;
+            mg_seq = s;
+            mg_e = e0;
+            mg_e1 = e1;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                mg_M[u] = -INFINITY;
+                mg_L[u] = 0.f;
+                mg_acc[u] = (f32x4)(0.f);
+            }
+        }
+        seq_announced = -1;
+    };
+    for (int idle = 0;;) {
+        // (1) publish
+        bool gate = !end_published && n_pub - n_cons < RING - 1;
+        if (gate && n_pub > 0) {
+            int last_tok = 0;
+#pragma unroll
+            for (int i = 0; i < RING; ++i)
+                if (i == (n_pub - 1) % RING) last_tok = ntok_of[i];
+            gate = lds_load_acquire(&sm.blk[(n_pub - 1) % RING]) + PUBLISH_AHEAD_BLOCKS >= ((last_tok + 31) >> 5);
+        }
+        if (gate) {
+            int id;
+            if (n_pub == 0) id = w;
+            else if (n_pub == 1) id = 2 * W - 1 - w;
+            else {
+                int got = 0;
+                if (lane == 0) got = atomicAdd(a.queue + hk, 1);
+                id = 2 * W + __builtin_amdgcn_readfirstlane(got);
+            }
+            const Unit un = fetch_unit(a, id);
+            const int slot = n_pub % RING;
+            if (lane == 0) {
+                sm.ring[slot].row_off = un.row - a.bt;
+                sm.ring[slot].seq0 = un.seq0;
+                sm.ring[slot].n_tok = un.n_tok;
+                sm.ring[slot].part_base = un.part_base;
+                sm.ring[slot].kind = un.kind;
+                sm.blk[slot] = 0;
+                sm.done[slot] = 0;
+            }
+#pragma unroll
+            for (int i = 0; i < RING; ++i)
+                if (i == slot) {
+                    seq0_of[i] = un.seq0;
+                    base_of[i] = un.part_base;
+                    ntok_of[i] = un.n_tok;
+                }
+            ++n_pub;
+            if (un.kind == 1) ++n_units;
+            else end_published = true;
+            if (lane == 0) lds_store_release(&sm.published, n_pub);
+            idle = 0;
+            continue;
+        }
+        // (2) combine a unit all streaming waves have left; needs the announce slot free
+        if (n_cons < n_units && seq_announced < 0 && lds_load_acquire(&sm.done[n_cons % RING]) == STREAM_WAVES) {
+            const int slot = n_cons % RING, par = n_cons & 1;
+            int seq0 = 0, part_base = 0;
+#pragma unroll
+            for (int i = 0; i < RING; ++i)
+                if (i == slot) {
+                    seq0 = seq0_of[i];
+                    part_base = base_of[i];
+                }
+            if (seq_stored >= 0) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's earlier stores are written through
+                if (lane == 0) old = atomicAdd(a.counters + (int64_t)seq_stored * a.n_kv_heads + hk, 1);
+                seq_announced = seq_stored;
+            }
+            for (int idx = lane; idx < total; idx += 64) {
+                const int r = idx / (D / 4), d4 = idx % (D / 4);
+                float mw[STREAM_WAVES], M = -INFINITY;
+#pragma unroll
+                for (int v = 0; v < STREAM_WAVES; ++v) {
+                    mw[v] = sm.ml[par][v][r].x;
+                    M = fmaxf(M, mw[v]);
+                }
+                float L = 0.f;
+                f32x4 acc = (f32x4)(0.f);
+#pragma unroll
+                for (int v = 0; v < STREAM_WAVES; ++v) {
+                    const float wg = mw[v] == -INFINITY ? 0.f : fast_exp2(mw[v] - M);  // a wave may have had no block
+                    L += wg * sm.ml[par][v][r].y;
+                    acc += wg * *(const f32x4*)&sm.o[par][v][r][4 * d4];
+                }
+                const int64_t row = (int64_t)part_base + hk * g + r;
+                coherent_store4(a.ws_o + row * D + 4 * d4, acc);
+                if (d4 == 0) coherent_store2((float*)(a.ws_ml + row), M, L);
+            }
+            seq_stored = seq0;
+            ++n_cons;
+            if (lane == 0) lds_store_release(&sm.consumed, n_cons);  // the slot has been read
+            idle = 0;
+            continue;
+        }
+        // (3) merges
+        if (mg_seq >= 0) {
+            merge_round();
+            idle = 0;
+            continue;
+        }
+        if (seq_announced >= 0) {
+            settle();
+            idle = 0;
+            continue;
+        }
+        if (end_published && n_cons == n_units) {
+            if (seq_stored < 0) break;
+            // the last unit: announce it, then come round again to settle and merge
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0) old = atomicAdd(a.counters + (int64_t)seq_stored * a.n_kv_heads + hk, 1);
+            seq_announced = seq_stored;
+            seq_stored = -1;
+            continue;
+        }
+        if (lds_load_acquire(&sm.failed)) return;
+        if (++idle >= SPIN_LIMIT) {
+            lds_store_release(&sm.failed, 1);
+            a.queue[a.n_kv_heads + 1] = 1;
+            return;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void decode_private_kernel(StepArgs a) {
+    __shared__ __attribute__((aligned(16))) SpecSmem<D> sm;
+    const int hk = blockIdx.x % a.n_kv_heads;
+    const int w = blockIdx.x / a.n_kv_heads;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#ifdef TAPER_WG_TRACE
+    long long* trace = (long long*)a.lse;
+    a.lse = nullptr;
+    if (threadIdx.x == 0) trace[3 * blockIdx.x] = wall_clock64();
+#endif
+    if (threadIdx.x == 0) {
+        sm.published = 0;
+        sm.consumed = 0;
+        sm.failed = 0;
+    }
+    __syncthreads();
+    if (wave == STREAM_WAVES)
+        control_wave<D>(a, hk, sm, w);
+    else
+        stream_wave<D>(a, hk, sm, wave);
+    __syncthreads();
+#ifdef TAPER_WG_TRACE
+    if (threadIdx.x == 0) {
+        trace[3 * blockIdx.x + 1] = wall_clock64();
+        trace[3 * blockIdx.x + 2] = 0;
+    }
+#endif
+    // the last workgroup to leave puts the queue back to zero for the next launch
+    if (threadIdx.x == 0 && atomicAdd(a.queue + a.n_kv_heads, 1) == (int)gridDim.x - 1) {
+        for (int h = 0; h <= a.n_kv_heads; ++h) a.queue[h] = 0;
+    }
+}
+
 // Physical slot of every logical position, from the device copy of the plan.
 __global__ __launch_bounds__(256) void resolve_slots_kernel(StepArgs a, int64_t* slots, int64_t stride) {
     const int s = blockIdx.x;
@@ -814,13 +1284,13 @@ hipError_t launch_decode(const StepArgs& a, hipStream_t s) {
     const dim3 grid(a.wgs_per_head * a.n_kv_heads), block(256);
     const int ntw = (a.max_row_tiles_shared + 3) / 4;
     if (a.head_dim == 128) {
-        if (ntw == 0) hipLaunchKernelGGL((decode_kernel<128, 0>), grid, block, 0, s, a);
+        if (ntw == 0) hipLaunchKernelGGL((decode_private_kernel<128>), grid, block, 0, s, a);
         else if (ntw == 1) hipLaunchKernelGGL((decode_kernel<128, 1>), grid, block, 0, s, a);
         else if (ntw == 2) hipLaunchKernelGGL((decode_kernel<128, 2>), grid, block, 0, s, a);
         else if (ntw == 3) hipLaunchKernelGGL((decode_kernel<128, 3>), grid, block, 0, s, a);
         else return hipErrorInvalidValue;
     } else if (a.head_dim == 64) {
-        if (ntw == 0) hipLaunchKernelGGL((decode_kernel<64, 0>), grid, block, 0, s, a);
+        if (ntw == 0) hipLaunchKernelGGL((decode_private_kernel<64>), grid, block, 0, s, a);
         else if (ntw == 1) hipLaunchKernelGGL((decode_kernel<64, 1>), grid, block, 0, s, a);
         else if (ntw == 2) hipLaunchKernelGGL((decode_kernel<64, 2>), grid, block, 0, s, a);
         else if (ntw == 3) hipLaunchKernelGGL((decode_kernel<64, 3>), grid, block, 0, s, a);
