@@ -86,8 +86,7 @@ typedef struct taper_ctx taper_ctx;   /* owns the partials workspace            
 typedef struct taper_plan taper_plan; /* owns host + device copies of the step's integer metadata */
 
 /* One unit of KV streaming: n_tokens tokens starting at block-table entry page0 of
- * row seq0, multiplied against the query rows of n_branch consecutive sequences.
- * Units are what workgroups take from the step's work queue, one at a time. */
+ * row seq0, multiplied against the query rows of n_branch consecutive sequences. */
 typedef struct {
     int32_t seq0;      /* first sequence; its block-table row supplies the pages    */
     int32_t n_branch;  /* sequences seq0..seq0+n_branch-1 share these tokens        */
@@ -96,7 +95,8 @@ typedef struct {
     int32_t part_base; /* first partial row; row of (kv head hk, branch b, head-in-group j)
                           = part_base + hk * n_branch * gqa + b * gqa + j           */
     int32_t kind;      /* 0 = shared prefix of a parallel request, 1 = private      */
-    int32_t reserved[2];
+    int32_t part;      /* workgroup share this item belongs to                      */
+    int32_t reserved;
 } taper_work_item;
 
 /* Where sequence s finds one of its partials: rows first_row + hk*rows_per_head + j */
@@ -114,12 +114,9 @@ typedef struct {
                                       marginal blocks (App. C), 0 for an empty branch       */
     const int32_t *group_start;    /* [n_groups + 1] CSR of requests over sequences         */
     int32_t n_items;
-    const taper_work_item *items;  /* [n_items] in queue order: the n_items_shared units of
-                                      kind 0 first, unit sizes shrinking towards the end    */
-    int32_t n_items_shared;
-    int32_t wgs_per_head;          /* W, workgroups per KV head the launch uses; workgroup w of a
-                                      head starts with units w and 2W - 1 - w and then takes
-                                      the next unclaimed one each time it finishes one       */
+    const taper_work_item *items;  /* [n_items], ordered by part                            */
+    int32_t n_parts_shared, n_parts_private;
+    const int32_t *part_start;     /* [n_parts_shared + n_parts_private + 1] CSR over items */
     const int32_t *merge_start;    /* [n_seqs + 1] CSR over merge entries                   */
     const taper_merge_entry *merge;
     int64_t n_partial_rows;
@@ -128,17 +125,12 @@ typedef struct {
 } taper_plan_view;
 
 typedef struct {
-    int32_t target_workgroups; /* 0 = default (what the device keeps resident at once); total
-                                  workgroups of the launch, split evenly over the KV heads  */
+    int32_t target_workgroups; /* 0 = default; workgroup shares the KV stream is cut into */
     int32_t share_prefix;      /* 1 = default: read each request's prefix once for all its
                                   branches; 0 = every branch streams the prefix by itself  */
     int32_t max_branches_per_item; /* 0 = default (24); wider requests are cut into sub-groups */
-    int32_t shared_cost_pct;   /* 0 = default (150): cost of a shared-prefix token relative to a
-                                  private one when sizing units                                */
-    int32_t min_unit_tokens;   /* 0 = default (256): smallest unit a segment is cut into      */
-    int32_t guide_pct;         /* 0 = default (200): a unit's cost is the work still unassigned
-                                  divided by (guide_pct / 100 * wgs_per_head), so units shrink
-                                  as the queue drains and all workgroups finish together      */
+    int32_t shared_cost_pct;   /* 0 = default (130): relative cost of a shared-prefix token when
+                                  cutting the work into equal shares                           */
 } taper_plan_options;
 
 TAPER_API int taper_create(const taper_attn_config *cfg /* host */, taper_ctx **out_ctx);
@@ -148,7 +140,7 @@ TAPER_API void taper_destroy(taper_ctx *ctx);
  * Index resolution for one decode step (paper: the engine's batch formation
  * precedes the forward pass, App. D "Serving engine"; which pages each query row
  * reads follows §3.1).  Validates the batch, derives the request CSR, page counts,
- * the queue of KV units and the merge map, copies them to the device on
+ * the list of KV chunks and the merge map, copies them to the device on
  * `hip_stream` (unless the context is host-only) and grows the context's
  * workspace if needed.  The host arrays are only read during the call.  One plan
  * serves every layer of the step.  Not safe to call concurrently on one ctx.

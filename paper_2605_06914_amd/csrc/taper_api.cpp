@@ -49,7 +49,6 @@ struct taper_ctx {
     void* ws = nullptr;  // workspace: [counters] int32 | [rows] float2 (m, l) | [rows][D] float
     int64_t ws_rows = 0;
     int64_t ws_counters = 0;
-    int resident_wgs[3] = {512, 512, 256};  // per kernel variant (1, 2, 3 row tiles per wave)
     std::vector<PlanBuffers> free_buffers;
 };
 
@@ -60,6 +59,7 @@ struct taper_plan {
     // device pointers into `dev`
     const int32_t* d_bt = nullptr;
     const taper_work_item* d_items = nullptr;
+    const int32_t* d_part_start = nullptr;
     const int32_t* d_merge_start = nullptr;
     const taper_merge_entry* d_merge = nullptr;
     const int32_t* d_prefix_len = nullptr;
@@ -105,11 +105,7 @@ int acquire_buffers(taper_ctx* ctx, size_t bytes, PlanBuffers* out) {
     return TAPER_OK;
 }
 
-// [ws_counters] arrival counters, then [n_kv_heads + 1] queue counters
-size_t ws_queue_offset(const taper_ctx* ctx) { return align_up((size_t)ctx->ws_counters * sizeof(int32_t), 256); }
-size_t ws_ml_offset(const taper_ctx* ctx) {
-    return ws_queue_offset(ctx) + align_up((size_t)(ctx->cfg.n_kv_heads + 1) * sizeof(int32_t), 256);
-}
+size_t ws_ml_offset(const taper_ctx* ctx) { return align_up((size_t)ctx->ws_counters * sizeof(int32_t), 256); }
 size_t ws_o_offset(const taper_ctx* ctx) {
     return ws_ml_offset(ctx) + align_up((size_t)ctx->ws_rows * sizeof(float2), 256);
 }
@@ -152,13 +148,13 @@ taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const vo
     a.lse = lse;
     a.bt = plan->d_bt;
     a.items = plan->d_items;
+    a.part_start = plan->d_part_start;
     a.merge_start = plan->d_merge_start;
     a.merge = plan->d_merge;
     a.prefix_len = plan->d_prefix_len;
     a.n_prefix_pages = plan->d_n_prefix_pages;
     a.ctx_len = plan->d_ctx_len;
     a.counters = (int32_t*)ctx->ws;
-    a.queue = (int32_t*)((char*)ctx->ws + ws_queue_offset(ctx));
     a.ws_ml = (float2*)((char*)ctx->ws + ws_ml_offset(ctx));
     a.ws_o = (float*)((char*)ctx->ws + ws_o_offset(ctx));
     a.bt_stride = plan->host.bt_stride;
@@ -167,8 +163,8 @@ taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const vo
     a.n_kv_heads = ctx->cfg.n_kv_heads;
     a.gqa = ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads;
     a.head_dim = ctx->cfg.head_dim;
-    a.n_items = (int32_t)plan->host.items.size();
-    a.wgs_per_head = plan->host.wgs_per_head;
+    a.n_parts_shared = plan->host.n_parts_shared;
+    a.n_parts_private = plan->host.n_parts_private;
     a.max_row_tiles_shared = plan->host.max_row_tiles_shared;
     a.scale_log2e = ctx->cfg.scale * 1.4426950408889634f;
     return a;
@@ -228,11 +224,6 @@ int taper_create(const taper_attn_config* cfg, taper_ctx** out_ctx) {
             delete ctx;
             return fail_hip(e, "hipSetDevice");
         }
-        e = taper::query_resident_wgs(cfg->device, cfg->head_dim, ctx->resident_wgs);
-        if (e != hipSuccess) {
-            delete ctx;
-            return fail_hip(e, "occupancy query");
-        }
     }
     *out_ctx = ctx;
     return TAPER_OK;
@@ -254,7 +245,7 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
     if (!plan) return fail(TAPER_ENOMEM, "host allocation failed");
     plan->ctx = ctx;
     std::string err;
-    int st = taper::build_host_plan(ctx->cfg, ctx->resident_wgs, n_seqs, block_table, bt_row_stride, branch_group, prefix_len,
+    int st = taper::build_host_plan(ctx->cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len,
                                     suffix_len, n_pool_pages, opts, &plan->host, &err);
     if (st != TAPER_OK) {
         delete plan;
@@ -265,7 +256,7 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
         return TAPER_OK;
     }
     const taper::HostPlan& h = plan->host;
-    // one image: bt | items | merge_start | merge | prefix_len | n_prefix_pages | ctx_len
+    // one image: bt | items | part_start | merge_start | merge | prefix_len | n_prefix_pages | ctx_len
     struct Piece {
         const void* src;
         size_t bytes;
@@ -274,6 +265,7 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
     std::vector<Piece> pieces = {
         {h.block_table.data(), h.block_table.size() * sizeof(int32_t), 0},
         {h.items.data(), h.items.size() * sizeof(taper_work_item), 0},
+        {h.part_start.data(), h.part_start.size() * sizeof(int32_t), 0},
         {h.merge_start.data(), h.merge_start.size() * sizeof(int32_t), 0},
         {h.merge.data(), h.merge.size() * sizeof(taper_merge_entry), 0},
         {h.prefix_len.data(), h.prefix_len.size() * sizeof(int32_t), 0},
@@ -307,11 +299,12 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
     char* d = (char*)plan->buf.dev;
     plan->d_bt = (const int32_t*)(d + pieces[0].off);
     plan->d_items = (const taper_work_item*)(d + pieces[1].off);
-    plan->d_merge_start = (const int32_t*)(d + pieces[2].off);
-    plan->d_merge = (const taper_merge_entry*)(d + pieces[3].off);
-    plan->d_prefix_len = (const int32_t*)(d + pieces[4].off);
-    plan->d_n_prefix_pages = (const int32_t*)(d + pieces[5].off);
-    plan->d_ctx_len = (const int32_t*)(d + pieces[6].off);
+    plan->d_part_start = (const int32_t*)(d + pieces[2].off);
+    plan->d_merge_start = (const int32_t*)(d + pieces[3].off);
+    plan->d_merge = (const taper_merge_entry*)(d + pieces[4].off);
+    plan->d_prefix_len = (const int32_t*)(d + pieces[5].off);
+    plan->d_n_prefix_pages = (const int32_t*)(d + pieces[6].off);
+    plan->d_ctx_len = (const int32_t*)(d + pieces[7].off);
     st = ensure_workspace(ctx, h.n_partial_rows, (int64_t)h.n_seqs * ctx->cfg.n_kv_heads);
     if (st != TAPER_OK) {
         std::string keep = g_last_error;
@@ -343,8 +336,9 @@ int taper_plan_export(const taper_plan* plan, taper_plan_view* v) {
     v->group_start = h.group_start.data();
     v->n_items = (int32_t)h.items.size();
     v->items = h.items.data();
-    v->n_items_shared = h.n_items_shared;
-    v->wgs_per_head = h.wgs_per_head;
+    v->n_parts_shared = h.n_parts_shared;
+    v->n_parts_private = h.n_parts_private;
+    v->part_start = h.part_start.data();
     v->merge_start = h.merge_start.data();
     v->merge = h.merge.data();
     v->n_partial_rows = h.n_partial_rows;

@@ -15,7 +15,8 @@ struct StepArgs {
     void* out;                 // bf16 [S][Hq][D]
     float* lse;                // f32 [S][Hq] or null
     const int32_t* bt;         // [S][bt_stride]
-    const taper_work_item* items;  // the work queue, in claim order
+    const taper_work_item* items;
+    const int32_t* part_start;
     const int32_t* merge_start;
     const taper_merge_entry* merge;
     const int32_t* prefix_len;
@@ -24,19 +25,15 @@ struct StepArgs {
     float2* ws_ml;             // [n_partial_rows] (running max in log2 units, sum)
     float* ws_o;               // [n_partial_rows][D] unnormalised
     int32_t* counters;         // [n_seqs][n_kv_heads] partials delivered so far; zero between launches
-    int32_t* queue;            // [n_kv_heads] units claimed beyond the pre-assigned ones, then [1] workgroups
-                               // that have left the kernel; zero between launches
     int32_t bt_stride;
     int32_t n_seqs;
     int32_t n_q_heads, n_kv_heads, gqa, head_dim;
-    int32_t n_items;
-    int32_t wgs_per_head;
+    int32_t n_parts_shared, n_parts_private;
     int32_t max_row_tiles_shared;
     float scale_log2e;         // scale * log2(e)
 };
 
 hipError_t launch_decode(const StepArgs& a, hipStream_t s);
-hipError_t query_resident_wgs(int device, int head_dim, int out[3]);
 hipError_t launch_resolve_slots(const StepArgs& a, int64_t* slots, int64_t stride, hipStream_t s);
 
 }  // namespace taper

@@ -50,40 +50,53 @@ struct Segment {
     int32_t seq0, n_branch, page0, n_tokens, kind;
 };
 
-// Cuts `segs` (in the given order) into queue units.  `remaining` is the cost (in
-// private-token equivalents) of everything not yet cut, this list included; a unit
-// costs about remaining / slots, never less than min_cost, so units shrink as the
-// queue drains (guided self-scheduling).  A unit is a multiple of `blk` tokens from
-// its segment's start (except a segment's last unit) and never spans segments.
-void cut_units(const std::vector<Segment>& segs, int64_t w_pct, int blk, int64_t slots_x100, int64_t min_tokens,
-               int64_t* remaining, std::vector<taper_work_item>* items) {
+// Cut `segs` into workgroup shares of about `quota` blocks of `blk` tokens, at
+// multiples of `blk` tokens from each segment's start.  Appends items (tagged
+// with part ids starting at part_id0) and returns the number of shares used.
+int partition(const std::vector<Segment>& segs, int64_t quota, int blk, int part_id0,
+              std::vector<taper_work_item>* items) {
+    int64_t total_blocks = 0;
+    for (const Segment& s : segs) total_blocks += (s.n_tokens + blk - 1) / blk;
+    if (total_blocks == 0) return 0;
+    quota = std::max<int64_t>(1, quota);
+    const int64_t sliver = std::max<int64_t>(1, quota / 32);  // an item's fixed cost is about one block's time
+    int part = 0;
+    int64_t fill = 0;
     for (const Segment& s : segs) {
-        int64_t left = s.n_tokens, off = 0;  // tokens
-        const int64_t seg_min = s.kind == 0 ? std::max<int64_t>(min_tokens, 64LL * s.n_branch) : min_tokens;
-        while (left > 0) {
-            int64_t want = *remaining * 100 / slots_x100;  // cost of this unit
-            want = want * 100 / w_pct;                      // tokens
-            want = std::max(want, seg_min);
-            want = (want + blk - 1) / blk * blk;
-            int64_t take = left <= want + want / 2 ? left : want;
+        int64_t remaining = (s.n_tokens + blk - 1) / blk, off = 0;
+        while (remaining > 0) {
+            int64_t room = quota - fill;
+            if (fill > 0 && room < sliver && room < remaining) {  // not worth a separate partial
+                ++part;
+                fill = 0;
+                continue;
+            }
+            int64_t take = std::min(remaining, std::max<int64_t>(room, 1));
+            if (remaining - take > 0 && remaining - take < sliver) take = remaining;
             taper_work_item it;
             std::memset(&it, 0, sizeof it);
             it.seq0 = s.seq0;
             it.n_branch = s.n_branch;
-            it.page0 = s.page0 + (int32_t)(off / 16);
-            it.n_tokens = (int32_t)take;
+            it.page0 = s.page0 + (int32_t)(off * blk / 16);
+            it.n_tokens = (int32_t)std::min<int64_t>(take * blk, s.n_tokens - off * blk);
             it.kind = s.kind;
+            it.part = part_id0 + part;
             items->push_back(it);
-            *remaining -= take * w_pct / 100;
-            left -= take;
+            fill += take;
             off += take;
+            remaining -= take;
+            if (fill >= quota) {
+                ++part;
+                fill = 0;
+            }
         }
     }
+    return fill > 0 ? part + 1 : part;
 }
 
 }  // namespace
 
-int build_host_plan(const taper_attn_config& cfg, const int resident_wgs[3], int n_seqs, const int32_t* block_table, int bt_row_stride,
+int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* block_table, int bt_row_stride,
                     const int32_t* branch_group, const int32_t* prefix_len, const int32_t* suffix_len,
                     int64_t n_pool_pages, const taper_plan_options* opts, HostPlan* out, std::string* err) {
     int st = validate_config(cfg, err);
@@ -102,6 +115,7 @@ int build_host_plan(const taper_attn_config& cfg, const int resident_wgs[3], int
     }
     const int P = cfg.page_size;
     const int g = cfg.n_q_heads / cfg.n_kv_heads;
+    int target_wgs = opts && opts->target_workgroups > 0 ? opts->target_workgroups : 512;
     const bool share_prefix = opts ? opts->share_prefix != 0 : true;
     int max_tiles = kMaxRowTilesPerItem;
     int cap_branches = std::min(64, std::max(2, max_tiles * 16 / g));  // 64: per-branch flags of the shared kernel
@@ -210,34 +224,30 @@ int build_host_plan(const taper_attn_config& cfg, const int resident_wgs[3], int
         }
     }
 
-    // ---- the work queue.  Workgroups are persistent: each takes a unit, streams it, writes a
-    // partial and takes the next unclaimed unit, so slow and fast units even out by themselves.
-    // Expensive units go first (shared prefixes, widest first), then private tokens, long
-    // segments first; within that order unit sizes shrink with the work still unassigned.
-    auto longer_first = [](const Segment& x, const Segment& y) {
-        if (x.n_branch != y.n_branch) return x.n_branch > y.n_branch;
-        if (x.n_tokens != y.n_tokens) return x.n_tokens > y.n_tokens;
-        if (x.seq0 != y.seq0) return x.seq0 < y.seq0;
-        return x.page0 < y.page0;
-    };
-    std::sort(shared.begin(), shared.end(), longer_first);
-    std::sort(priv.begin(), priv.end(), longer_first);
-    int tiles = 0;
-    for (const Segment& s : shared) tiles = std::max(tiles, (s.n_branch * g + 15) / 16);
-    p.max_row_tiles_shared = tiles;
-    int target_wgs = opts && opts->target_workgroups > 0 ? opts->target_workgroups
-                                                         : resident_wgs[tiles <= 4 ? 0 : (tiles <= 8 ? 1 : 2)];
-    p.wgs_per_head = std::min(8192, std::max(1, target_wgs / cfg.n_kv_heads));
-    const int64_t w_pct = opts && opts->shared_cost_pct > 0 ? opts->shared_cost_pct : 150;
-    const int64_t min_tokens = opts && opts->min_unit_tokens > 0 ? opts->min_unit_tokens : 256;
-    const int64_t guide_pct = opts && opts->guide_pct > 0 ? opts->guide_pct : 200;
-    int64_t remaining = 0;
-    for (const Segment& s : shared) remaining += (int64_t)s.n_tokens * w_pct / 100;
-    for (const Segment& s : priv) remaining += s.n_tokens;
-    const int64_t slots_x100 = std::max<int64_t>(100, guide_pct * p.wgs_per_head);
-    cut_units(shared, w_pct, kSharedBlockTokens, slots_x100, min_tokens, &remaining, &p.items);
-    p.n_items_shared = (int)p.items.size();
-    cut_units(priv, 100, kPrivateBlockTokens, slots_x100, min_tokens, &remaining, &p.items);
+    // ---- workgroup shares: both kinds run in one launch and should finish together.  A workgroup of
+    // the shared kind keeps fewer bytes in flight than one of the private kind and so gets a smaller
+    // slice of a saturated memory system: its tokens are weighted by shared_cost_pct / 100.
+    const int64_t w_pct = opts && opts->shared_cost_pct > 0 ? opts->shared_cost_pct : 130;
+    int64_t tok_shared = 0, tok_priv = 0;
+    for (const Segment& s : shared) tok_shared += s.n_tokens;
+    for (const Segment& s : priv) tok_priv += s.n_tokens;
+    const int64_t tok_total = tok_shared + tok_priv;
+    const int parts_total = std::max(1, target_wgs / cfg.n_kv_heads);
+    // quota of the private kind in tokens; the shared kind gets quota * 100 / w_pct
+    int64_t quota_tokens = ((tok_shared * w_pct + 99) / 100 + tok_priv + parts_total - 1) / parts_total;
+    quota_tokens = std::max<int64_t>(kSharedBlockTokens, (quota_tokens + kSharedBlockTokens - 1) / kSharedBlockTokens * kSharedBlockTokens);
+    for (;;) {  // never more shares than asked for: an extra one would run after all the others
+        p.items.clear();
+        const int64_t quota_shared = std::max<int64_t>(1, quota_tokens * 100 / w_pct / kSharedBlockTokens);
+        p.n_parts_shared = partition(shared, quota_shared, kSharedBlockTokens, 0, &p.items);
+        p.n_parts_private = partition(priv, quota_tokens / kPrivateBlockTokens, kPrivateBlockTokens, p.n_parts_shared, &p.items);
+        if (p.n_parts_shared + p.n_parts_private <= parts_total || quota_tokens >= tok_total * 2) break;
+        quota_tokens += kSharedBlockTokens;
+    }
+    const int n_parts = p.n_parts_shared + p.n_parts_private;
+    p.part_start.assign(n_parts + 1, 0);
+    for (const taper_work_item& it : p.items) p.part_start[it.part + 1]++;
+    for (int i = 0; i < n_parts; ++i) p.part_start[i + 1] += p.part_start[i];
 
     // ---- partial rows and merge map
     std::vector<std::vector<taper_merge_entry>> per_seq(n_seqs);
@@ -249,6 +259,7 @@ int build_host_plan(const taper_attn_config& cfg, const int resident_wgs[3], int
         }
         it.part_base = (int32_t)rows;
         const int rph = it.n_branch * g;
+        if (it.kind == 0) p.max_row_tiles_shared = std::max(p.max_row_tiles_shared, (rph + 15) / 16);
         for (int b = 0; b < it.n_branch; ++b) per_seq[it.seq0 + b].push_back({it.part_base + b * g, rph});
         rows += (int64_t)rph * cfg.n_kv_heads;
     }

@@ -1,5 +1,5 @@
 // Host-side index resolution for one decode step: validation, request CSR,
-// the queue of KV units and the merge map.  Pure integer C++, no HIP.
+// KV chunk list, workgroup shares and merge map.  Pure integer C++, no HIP.
 #pragma once
 #include <cstdint>
 #include <string>
@@ -19,9 +19,9 @@ struct HostPlan {
     std::vector<int32_t> block_table;  // [n_seqs * bt_stride], entries past a row's pages set to -1
     std::vector<int32_t> prefix_len, suffix_len, ctx_len, n_prefix_pages, n_suffix_pages;
     std::vector<int32_t> group_start;  // [n_groups + 1]
-    std::vector<taper_work_item> items;  // queue order: shared units first, sizes shrinking
-    int n_items_shared = 0;
-    int wgs_per_head = 0;  // workgroups per KV head of the launch
+    std::vector<taper_work_item> items;
+    int n_parts_shared = 0, n_parts_private = 0;
+    std::vector<int32_t> part_start;  // [n_parts + 1]
     std::vector<int32_t> merge_start; // [n_seqs + 1]
     std::vector<taper_merge_entry> merge;
     int64_t n_partial_rows = 0;
@@ -30,9 +30,7 @@ struct HostPlan {
 };
 
 // Returns TAPER_OK or a negative status; `err` receives a message on failure.
-// `resident_wgs[i]`: workgroups the device keeps resident at once when the widest shared unit
-// has at most 4*(i+1) row tiles (the kernel variant for it differs in registers per wave).
-int build_host_plan(const taper_attn_config& cfg, const int resident_wgs[3], int n_seqs, const int32_t* block_table, int bt_row_stride,
+int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* block_table, int bt_row_stride,
                     const int32_t* branch_group, const int32_t* prefix_len, const int32_t* suffix_len,
                     int64_t n_pool_pages, const taper_plan_options* opts, HostPlan* out, std::string* err);
 
