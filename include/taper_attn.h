@@ -95,7 +95,7 @@ typedef struct {
     int32_t part_base; /* first partial row; row of (kv head hk, branch b, head-in-group j)
                           = part_base + hk * n_branch * gqa + b * gqa + j           */
     int32_t kind;      /* 0 = shared prefix of a parallel request, 1 = private      */
-    int32_t part;      /* workgroup share this item belongs to                      */
+    int32_t part;      /* workgroup share this item belongs to; n_parts for pool items */
     int32_t reserved;
 } taper_work_item;
 
@@ -114,7 +114,8 @@ typedef struct {
                                       marginal blocks (App. C), 0 for an empty branch       */
     const int32_t *group_start;    /* [n_groups + 1] CSR of requests over sequences         */
     int32_t n_items;
-    const taper_work_item *items;  /* [n_items], ordered by part                            */
+    const taper_work_item *items;  /* [n_items], ordered by part, then the n_pool_items pool items */
+    int32_t n_pool_items;
     int32_t n_parts_shared, n_parts_private;
     const int32_t *part_start;     /* [n_parts_shared + n_parts_private + 1] CSR over items */
     const int32_t *merge_start;    /* [n_seqs + 1] CSR over merge entries                   */
@@ -128,9 +129,19 @@ typedef struct {
     int32_t target_workgroups; /* 0 = default; workgroup shares the KV stream is cut into */
     int32_t share_prefix;      /* 1 = default: read each request's prefix once for all its
                                   branches; 0 = every branch streams the prefix by itself  */
-    int32_t max_branches_per_item; /* 0 = default (24); wider requests are cut into sub-groups */
-    int32_t shared_cost_pct;   /* 0 = default (130): relative cost of a shared-prefix token when
-                                  cutting the work into equal shares                           */
+    int32_t max_branches_per_item; /* 0 = default (8 row tiles: 16 branches at 8 query heads per KV
+                                      head); wider requests are cut into equal sub-groups of at
+                                      most this size; at most 12 row tiles                     */
+    int32_t shared_cost_pct;   /* 0 = default (200): cost of a shared-prefix token relative to a
+                                  private one when cutting the work into equal shares          */
+    int32_t shared_item_cost;  /* 0 = default (800): fixed cost of a shared-prefix item, in private
+                                  tokens' streaming time                                       */
+    int32_t private_item_cost; /* 0 = default (128): fixed cost of a private item, same unit      */
+    int32_t pool_pct;          /* 0 = default (25 when the step has shared-prefix work, else none):
+                                  percentage of the private tokens that no share owns; workgroups
+                                  that finish their share take them, an item at a time, so the
+                                  launch ends evenly.  -1 = none                                 */
+    int32_t pool_item_tokens;  /* 0 = default (512): size of the pool's items                     */
 } taper_plan_options;
 
 TAPER_API int taper_create(const taper_attn_config *cfg /* host */, taper_ctx **out_ctx);

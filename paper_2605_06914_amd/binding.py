@@ -47,6 +47,7 @@ class taper_plan_view(ctypes.Structure):
     _fields_ = [("n_seqs", ctypes.c_int32), ("n_groups", ctypes.c_int32), ("ctx_len", _I32P),
                 ("n_prefix_pages", _I32P), ("n_suffix_pages", _I32P), ("group_start", _I32P),
                 ("n_items", ctypes.c_int32), ("items", ctypes.POINTER(taper_work_item)),
+                ("n_pool_items", ctypes.c_int32),
                 ("n_parts_shared", ctypes.c_int32), ("n_parts_private", ctypes.c_int32), ("part_start", _I32P),
                 ("merge_start", _I32P), ("merge", ctypes.POINTER(taper_merge_entry)),
                 ("n_partial_rows", ctypes.c_int64), ("tokens_unique", ctypes.c_int64),
@@ -55,7 +56,9 @@ class taper_plan_view(ctypes.Structure):
 
 class taper_plan_options(ctypes.Structure):
     _fields_ = [("target_workgroups", ctypes.c_int32), ("share_prefix", ctypes.c_int32),
-                ("max_branches_per_item", ctypes.c_int32), ("shared_cost_pct", ctypes.c_int32)]
+                ("max_branches_per_item", ctypes.c_int32), ("shared_cost_pct", ctypes.c_int32),
+                ("shared_item_cost", ctypes.c_int32), ("private_item_cost", ctypes.c_int32),
+                ("pool_pct", ctypes.c_int32), ("pool_item_tokens", ctypes.c_int32)]
 
 
 class taper_probe_result(ctypes.Structure):
@@ -166,7 +169,7 @@ class Plan:
         return dict(n_seqs=S, n_groups=G, ctx_len=arr(v.ctx_len, S), n_prefix_pages=arr(v.n_prefix_pages, S),
                     n_suffix_pages=arr(v.n_suffix_pages, S), group_start=arr(v.group_start, G + 1),
                     items=items, item_fields=[f[0] for f in taper_work_item._fields_],
-                    n_parts_shared=v.n_parts_shared, n_parts_private=v.n_parts_private,
+                    n_pool_items=v.n_pool_items, n_parts_shared=v.n_parts_shared, n_parts_private=v.n_parts_private,
                     part_start=arr(v.part_start, n_parts + 1), merge_start=arr(v.merge_start, S + 1), merge=merge,
                     n_partial_rows=int(v.n_partial_rows), tokens_unique=int(v.tokens_unique),
                     tokens_logical=int(v.tokens_logical))
@@ -207,12 +210,14 @@ class Context:
 
     def plan_build(self, block_table, branch_group, prefix_len, suffix_len, n_pool_pages: int,
                    target_workgroups: int = 0, share_prefix: bool = True, max_branches_per_item: int = 0,
-                   shared_cost_pct: int = 0, stream=None) -> Plan:
+                   shared_cost_pct: int = 0, shared_item_cost: int = 0, private_item_cost: int = 0,
+                   pool_pct: int = 0, pool_item_tokens: int = 0, stream=None) -> Plan:
         bt = _i32(block_table)
         grp, pl, sl = _i32(branch_group), _i32(prefix_len), _i32(suffix_len)
         if bt.ndim != 2 or not (len(grp) == len(pl) == len(sl) == bt.shape[0]):
             raise TaperError(TAPER_EINVAL, "block_table must be [S, max_blocks] and the per-sequence arrays length S")
-        opts = taper_plan_options(target_workgroups, int(share_prefix), max_branches_per_item, shared_cost_pct)
+        opts = taper_plan_options(target_workgroups, int(share_prefix), max_branches_per_item, shared_cost_pct,
+                                  shared_item_cost, private_item_cost, pool_pct, pool_item_tokens)
         h = ctypes.c_void_p()
         st = 0 if self.cfg.device < 0 else _stream(stream)
         _check(load_library().taper_plan_build(self._h, bt.shape[0], bt.ctypes.data, bt.shape[1], grp.ctypes.data,

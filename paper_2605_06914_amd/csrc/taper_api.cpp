@@ -155,6 +155,9 @@ taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const vo
     a.n_prefix_pages = plan->d_n_prefix_pages;
     a.ctx_len = plan->d_ctx_len;
     a.counters = (int32_t*)ctx->ws;
+    a.pool_ctr = a.counters + (int64_t)plan->host.n_seqs * ctx->cfg.n_kv_heads;
+    a.pool_first = plan->host.part_start[plan->host.n_parts_shared + plan->host.n_parts_private];
+    a.n_pool_items = plan->host.n_pool_items;
     a.ws_ml = (float2*)((char*)ctx->ws + ws_ml_offset(ctx));
     a.ws_o = (float*)((char*)ctx->ws + ws_o_offset(ctx));
     a.bt_stride = plan->host.bt_stride;
@@ -174,7 +177,7 @@ int check_step(const taper_ctx* ctx, const taper_plan* plan) {
     if (!ctx || !plan) return fail(TAPER_EINVAL, "null ctx or plan");
     if (plan->ctx != ctx) return fail(TAPER_EINVAL, "plan was built on another context");
     if (ctx->host_only || !plan->buf.dev) return fail(TAPER_EHIP, "host-only context: no device work possible");
-    if (plan->host.n_partial_rows > ctx->ws_rows || (int64_t)plan->host.n_seqs * ctx->cfg.n_kv_heads > ctx->ws_counters)
+    if (plan->host.n_partial_rows > ctx->ws_rows || ((int64_t)plan->host.n_seqs + 1) * ctx->cfg.n_kv_heads > ctx->ws_counters)
         return fail(TAPER_EINVAL, "workspace smaller than the plan needs");
     return TAPER_OK;
 }
@@ -305,7 +308,7 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
     plan->d_prefix_len = (const int32_t*)(d + pieces[5].off);
     plan->d_n_prefix_pages = (const int32_t*)(d + pieces[6].off);
     plan->d_ctx_len = (const int32_t*)(d + pieces[7].off);
-    st = ensure_workspace(ctx, h.n_partial_rows, (int64_t)h.n_seqs * ctx->cfg.n_kv_heads);
+    st = ensure_workspace(ctx, h.n_partial_rows, ((int64_t)h.n_seqs + 1) * ctx->cfg.n_kv_heads);
     if (st != TAPER_OK) {
         std::string keep = g_last_error;
         taper_plan_free(plan);
@@ -336,6 +339,7 @@ int taper_plan_export(const taper_plan* plan, taper_plan_view* v) {
     v->group_start = h.group_start.data();
     v->n_items = (int32_t)h.items.size();
     v->items = h.items.data();
+    v->n_pool_items = h.n_pool_items;
     v->n_parts_shared = h.n_parts_shared;
     v->n_parts_private = h.n_parts_private;
     v->part_start = h.part_start.data();

@@ -25,6 +25,8 @@ struct StepArgs {
     float2* ws_ml;             // [n_partial_rows] (running max in log2 units, sum)
     float* ws_o;               // [n_partial_rows][D] unnormalised
     int32_t* counters;         // [n_seqs][n_kv_heads] partials delivered so far; zero between launches
+    int32_t* pool_ctr;         // [n_kv_heads] pool items taken so far; zero between launches
+    int32_t pool_first, n_pool_items;  // the pool: items [pool_first, pool_first + n_pool_items)
     int32_t bt_stride;
     int32_t n_seqs;
     int32_t n_q_heads, n_kv_heads, gqa, head_dim;

@@ -40,10 +40,11 @@ DEV float max4(f32x4 v) { return fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])); }
 // Scores of invalid tokens of a chunk's last 32-token block -> -inf.
 // sx: tokens 4*qd+i of the block's first page, sy: of its second page.
 DEV void mask_tail(f32x4& sx, f32x4& sy, int qd, int n_valid) {
+    const int t = n_valid - 4 * qd;  // this lane's tokens i (first page) and 16 + i (second page) are valid below t
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        if (4 * qd + i >= n_valid) sx[i] = -INFINITY;
-        if (16 + 4 * qd + i >= n_valid) sy[i] = -INFINITY;
+        if (i >= t) sx[i] = -INFINITY;
+        if (16 + i >= t) sy[i] = -INFINITY;
     }
 }
 
@@ -205,10 +206,12 @@ struct PrivateSmem {
     float o[4][16][D + 4];
     float2 ml[4][16];
     int last;
+    int pick;  // pool item a workgroup has taken
 };
 
+// One private item: a chunk of one sequence's own tokens, for kv head hk.
 template <int D>
-DEV void private_path(const StepArgs& a, const int part, const int hk, PrivateSmem<D>& sm) {
+DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem<D>& sm) {
     constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D;
     auto& sm_o = sm.o;
     auto& sm_ml = sm.ml;
@@ -220,9 +223,7 @@ DEV void private_path(const StepArgs& a, const int part, const int hk, PrivateSm
     const int64_t page_elems = 2LL * Hkv * TILE;
     const float c = a.scale_log2e;
     const int koff = lane * 8, voff = qd * (4 * D) + n * 4;
-
-    const int it0 = a.part_start[part], it1 = a.part_start[part + 1];
-    for (int it = it0; it < it1; ++it) {
+    {
         const taper_work_item item = a.items[it];
         const int32_t* __restrict__ row = a.bt + (int64_t)item.seq0 * a.bt_stride + item.page0;
         const int n_tok = item.n_tokens;
@@ -324,6 +325,33 @@ DEV void private_path(const StepArgs& a, const int part, const int hk, PrivateSm
         if (threadIdx.x == 0) sm.last = arrive_last(a, item.seq0, hk);
         __syncthreads();
         if (sm.last) merge_rows<D, 1>(a, item.seq0, hk, threadIdx.x, 256);
+    }
+}
+
+// The private items of a workgroup: those of its share [it0, it1) in order, then whatever it
+// can take from its kv head's pool.  Every workgroup makes exactly one claim past the end of
+// the pool; the one that makes the last of those puts the counter back to zero for the next
+// launch.
+template <int D>
+DEV void private_items(const StepArgs& a, int it0, const int it1, const int hk, PrivateSmem<D>& sm) {
+    const int wgs_per_head = gridDim.x / a.n_kv_heads;
+    for (;;) {
+        int it = it0;
+        if (it0 < it1) {
+            ++it0;
+        } else {
+            if (a.n_pool_items == 0) return;
+            if (threadIdx.x == 0) sm.pick = atomicAdd(a.pool_ctr + hk, 1);
+            __syncthreads();
+            const int i = sm.pick;
+            __syncthreads();
+            if (i >= a.n_pool_items) {
+                if (threadIdx.x == 0 && i == a.n_pool_items + wgs_per_head - 1) a.pool_ctr[hk] = 0;
+                return;
+            }
+            it = a.pool_first + i;
+        }
+        private_item<D>(a, it, hk, sm);
     }
 }
 
@@ -512,20 +540,25 @@ __global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void decode_kernel(StepArg
     __shared__ __attribute__((aligned(16))) char smem_raw[sizeof(Smem)];
     const int part = blockIdx.x / a.n_kv_heads;
     const int hk = blockIdx.x % a.n_kv_heads;
-#ifdef TAPER_WG_TRACE  // development builds only: per-workgroup start/end clock into the lse buffer
-    StepArgs b = a;
-    b.lse = nullptr;
-    if (threadIdx.x == 0) ((long long*)a.lse)[2 * blockIdx.x] = wall_clock64();
-    if (part < a.n_parts_shared)
-        shared_path<D, NTW>(b, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
-    else
-        private_path<D>(b, part, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
-    if (threadIdx.x == 0) ((long long*)a.lse)[2 * blockIdx.x + 1] = wall_clock64();
-#else
-    if (part < a.n_parts_shared)
+#ifdef TAPER_WG_TRACE  // development builds only: per-workgroup clocks (start, own share done, left) into the lse buffer
+    long long* trace = (long long*)a.lse;
+    a.lse = nullptr;
+    if (threadIdx.x == 0) trace[3 * blockIdx.x] = wall_clock64();
+#endif
+    int it0 = 0, it1 = 0;  // private items of this workgroup's share
+    if (part < a.n_parts_shared) {
         shared_path<D, NTW>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
-    else
-        private_path<D>(a, part, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
+        __syncthreads();
+    } else {
+        it0 = a.part_start[part];
+        it1 = a.part_start[part + 1];
+    }
+#ifdef TAPER_WG_TRACE
+    if (threadIdx.x == 0) trace[3 * blockIdx.x + 1] = wall_clock64();  // shared share done / private share about to start
+#endif
+    private_items<D>(a, it0, it1, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
+#ifdef TAPER_WG_TRACE
+    if (threadIdx.x == 0) trace[3 * blockIdx.x + 2] = wall_clock64();
 #endif
 }
 

@@ -50,29 +50,38 @@ struct Segment {
     int32_t seq0, n_branch, page0, n_tokens, kind;
 };
 
-// Cut `segs` into workgroup shares of about `quota` blocks of `blk` tokens, at
-// multiples of `blk` tokens from each segment's start.  Appends items (tagged
-// with part ids starting at part_id0) and returns the number of shares used.
-int partition(const std::vector<Segment>& segs, int64_t quota, int blk, int part_id0,
+// Cost model of a workgroup share, in units of one private token's streaming time: an item of
+// n tokens costs fixed + n * per_token_pct / 100, `fixed` covering what an item costs beyond
+// streaming its tokens (query load, pipeline fill, partial rows, arrival, merges).
+struct Cost {
+    int64_t per_token_pct, fixed;
+};
+
+// Cuts `segs` into workgroup shares of about `quota` cost units, at multiples of `blk` tokens
+// from each segment's start.  Appends items (tagged with part ids starting at part_id0) and
+// returns the number of shares used.
+int partition(const std::vector<Segment>& segs, int64_t quota, int blk, const Cost cost, int part_id0,
               std::vector<taper_work_item>* items) {
-    int64_t total_blocks = 0;
-    for (const Segment& s : segs) total_blocks += (s.n_tokens + blk - 1) / blk;
-    if (total_blocks == 0) return 0;
+    int64_t total_tokens = 0;
+    for (const Segment& s : segs) total_tokens += s.n_tokens;
+    if (total_tokens == 0) return 0;
     quota = std::max<int64_t>(1, quota);
-    const int64_t sliver = std::max<int64_t>(1, quota / 32);  // an item's fixed cost is about one block's time
+    const int64_t blk_cost = std::max<int64_t>(1, blk * cost.per_token_pct / 100);
+    // a piece is only worth an item of its own if its streaming outweighs the item's fixed cost
+    const int64_t min_blocks = std::max<int64_t>(1, (cost.fixed + blk_cost - 1) / blk_cost);
     int part = 0;
     int64_t fill = 0;
     for (const Segment& s : segs) {
-        int64_t remaining = (s.n_tokens + blk - 1) / blk, off = 0;
+        int64_t remaining = (s.n_tokens + blk - 1) / blk, off = 0;  // blocks
         while (remaining > 0) {
-            int64_t room = quota - fill;
-            if (fill > 0 && room < sliver && room < remaining) {  // not worth a separate partial
+            const int64_t room = (quota - fill - cost.fixed) / blk_cost;  // blocks that still fit this share
+            if (fill > 0 && room < remaining && room < min_blocks) {        // start the next share instead
                 ++part;
                 fill = 0;
                 continue;
             }
             int64_t take = std::min(remaining, std::max<int64_t>(room, 1));
-            if (remaining - take > 0 && remaining - take < sliver) take = remaining;
+            if (remaining - take > 0 && remaining - take < min_blocks) take = remaining;  // no sliver left behind
             taper_work_item it;
             std::memset(&it, 0, sizeof it);
             it.seq0 = s.seq0;
@@ -82,7 +91,7 @@ int partition(const std::vector<Segment>& segs, int64_t quota, int blk, int part
             it.kind = s.kind;
             it.part = part_id0 + part;
             items->push_back(it);
-            fill += take;
+            fill += cost.fixed + take * blk_cost;
             off += take;
             remaining -= take;
             if (fill >= quota) {
@@ -117,9 +126,11 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
     const int g = cfg.n_q_heads / cfg.n_kv_heads;
     int target_wgs = opts && opts->target_workgroups > 0 ? opts->target_workgroups : 512;
     const bool share_prefix = opts ? opts->share_prefix != 0 : true;
-    int max_tiles = kMaxRowTilesPerItem;
-    int cap_branches = std::min(64, std::max(2, max_tiles * 16 / g));  // 64: per-branch flags of the shared kernel
-    if (opts && opts->max_branches_per_item > 0) cap_branches = std::max(1, std::min(cap_branches, opts->max_branches_per_item));
+    // A shared item of up to 8 row tiles runs with two workgroups per compute unit; up to 12 tiles
+    // are possible, with one.  64: per-branch flags of the shared kernel.
+    const int hard_cap = std::min(64, std::max(2, kMaxRowTilesPerItem * 16 / g));
+    int cap_branches = std::min(hard_cap, std::max(2, 8 * 16 / g));
+    if (opts && opts->max_branches_per_item > 0) cap_branches = std::max(1, std::min(hard_cap, opts->max_branches_per_item));
 
     HostPlan& p = *out;
     p = HostPlan();
@@ -226,28 +237,81 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
 
     // ---- workgroup shares: both kinds run in one launch and should finish together.  A workgroup of
     // the shared kind keeps fewer bytes in flight than one of the private kind and so gets a smaller
-    // slice of a saturated memory system: its tokens are weighted by shared_cost_pct / 100.
-    const int64_t w_pct = opts && opts->shared_cost_pct > 0 ? opts->shared_cost_pct : 130;
-    int64_t tok_shared = 0, tok_priv = 0;
-    for (const Segment& s : shared) tok_shared += s.n_tokens;
-    for (const Segment& s : priv) tok_priv += s.n_tokens;
-    const int64_t tok_total = tok_shared + tok_priv;
+    // slice of a saturated memory system: its tokens are weighted by shared_cost_pct / 100.  Every
+    // item also has a fixed cost (a shared item's is large: rows of several branches to store, and
+    // the merges of all branches it completes).
+    const Cost cost_shared = {opts && opts->shared_cost_pct > 0 ? opts->shared_cost_pct : 200,
+                              opts && opts->shared_item_cost > 0 ? opts->shared_item_cost : 800};
+    const Cost cost_priv = {100, opts && opts->private_item_cost > 0 ? opts->private_item_cost : 128};
+    int64_t cost_total = 0;
+    for (const Segment& s : shared) {
+        cost_total += cost_shared.fixed + (int64_t)s.n_tokens * cost_shared.per_token_pct / 100;
+    }
+    for (const Segment& s : priv) {
+        cost_total += cost_priv.fixed + s.n_tokens;
+    }
     const int parts_total = std::max(1, target_wgs / cfg.n_kv_heads);
-    // quota of the private kind in tokens; the shared kind gets quota * 100 / w_pct
-    int64_t quota_tokens = ((tok_shared * w_pct + 99) / 100 + tok_priv + parts_total - 1) / parts_total;
-    quota_tokens = std::max<int64_t>(kSharedBlockTokens, (quota_tokens + kSharedBlockTokens - 1) / kSharedBlockTokens * kSharedBlockTokens);
+    // ---- the pool: private tokens no share owns.  No cost model predicts the shares' running times
+    // to better than some ten percent (the kinds' speeds depend on the mix, page placement matters),
+    // so the shares are cut a little short and every workgroup that finishes its share takes items
+    // from the pool until it is empty.  Pool items are small: the last one bounds the tail.
+    // Without shared-prefix work the shares are alike and end within a few percent of each other:
+    // a pool would only add items.
+    const int pool_pct = opts && opts->pool_pct != 0 ? std::max(0, std::min(90, opts->pool_pct)) : (shared.empty() ? 0 : 25);
+    const int pool_item_tokens =
+        std::max(kPrivateBlockTokens, (opts && opts->pool_item_tokens > 0 ? opts->pool_item_tokens : 512) / kPrivateBlockTokens * kPrivateBlockTokens);
+    std::vector<Segment> pool;
+    {
+        int64_t tok_priv = 0;
+        for (const Segment& s : priv) tok_priv += s.n_tokens;
+        int64_t want = tok_priv * pool_pct / 100;
+        while (want >= kPrivateBlockTokens && !priv.empty()) {
+            Segment& s = priv.back();
+            if (s.n_tokens <= want + kPrivateBlockTokens) {  // the whole segment
+                want -= s.n_tokens;
+                cost_total -= cost_priv.fixed + s.n_tokens;
+                pool.push_back(s);
+                priv.pop_back();
+            } else {  // its tail, from a block boundary
+                const int keep = (int)((s.n_tokens - want + kPrivateBlockTokens - 1) / kPrivateBlockTokens * kPrivateBlockTokens);
+                if (keep < s.n_tokens) {
+                    pool.push_back({s.seq0, s.n_branch, s.page0 + keep / 16, s.n_tokens - keep, s.kind});
+                    cost_total -= s.n_tokens - keep;
+                    s.n_tokens = keep;
+                }
+                want = 0;
+            }
+        }
+        std::reverse(pool.begin(), pool.end());
+    }
+    int64_t quota = std::max<int64_t>(kSharedBlockTokens, (cost_total + parts_total - 1) / parts_total);
     for (;;) {  // never more shares than asked for: an extra one would run after all the others
         p.items.clear();
-        const int64_t quota_shared = std::max<int64_t>(1, quota_tokens * 100 / w_pct / kSharedBlockTokens);
-        p.n_parts_shared = partition(shared, quota_shared, kSharedBlockTokens, 0, &p.items);
-        p.n_parts_private = partition(priv, quota_tokens / kPrivateBlockTokens, kPrivateBlockTokens, p.n_parts_shared, &p.items);
-        if (p.n_parts_shared + p.n_parts_private <= parts_total || quota_tokens >= tok_total * 2) break;
-        quota_tokens += kSharedBlockTokens;
+        p.n_parts_shared = partition(shared, quota, kSharedBlockTokens, cost_shared, 0, &p.items);
+        p.n_parts_private = partition(priv, quota, kPrivateBlockTokens, cost_priv, p.n_parts_shared, &p.items);
+        if (p.n_parts_shared + p.n_parts_private <= parts_total || quota >= cost_total * 2 + 4096) break;
+        quota += std::max<int64_t>(16, quota / 256);
     }
     const int n_parts = p.n_parts_shared + p.n_parts_private;
     p.part_start.assign(n_parts + 1, 0);
     for (const taper_work_item& it : p.items) p.part_start[it.part + 1]++;
     for (int i = 0; i < n_parts; ++i) p.part_start[i + 1] += p.part_start[i];
+    for (const Segment& s : pool) {  // pool items follow the shares' items; their `part` is n_parts
+        const int k = (s.n_tokens + pool_item_tokens - 1) / pool_item_tokens;
+        const int piece = ((s.n_tokens + k - 1) / k + kPrivateBlockTokens - 1) / kPrivateBlockTokens * kPrivateBlockTokens;
+        for (int off = 0; off < s.n_tokens; off += piece) {
+            taper_work_item it;
+            std::memset(&it, 0, sizeof it);
+            it.seq0 = s.seq0;
+            it.n_branch = 1;
+            it.page0 = s.page0 + off / 16;
+            it.n_tokens = std::min(piece, s.n_tokens - off);
+            it.kind = 1;
+            it.part = n_parts;
+            p.items.push_back(it);
+        }
+    }
+    p.n_pool_items = (int)p.items.size() - p.part_start[n_parts];
 
     // ---- partial rows and merge map
     std::vector<std::vector<taper_merge_entry>> per_seq(n_seqs);

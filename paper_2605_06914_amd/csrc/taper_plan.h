@@ -21,6 +21,7 @@ struct HostPlan {
     std::vector<int32_t> group_start;  // [n_groups + 1]
     std::vector<taper_work_item> items;
     int n_parts_shared = 0, n_parts_private = 0;
+    int n_pool_items = 0;  // items after the shares' items, owned by no share
     std::vector<int32_t> part_start;  // [n_parts + 1]
     std::vector<int32_t> merge_start; // [n_seqs + 1]
     std::vector<taper_merge_entry> merge;

@@ -133,9 +133,14 @@ def check_plan_against_oracle(st, **kw):
     for s, c in enumerate(cover):
         assert np.all(c == 1), f"sequence {s} not covered exactly once"
     # parts partition the items; partial rows are disjoint; merge map lists each sequence's items
+    # after them the pool: private items that belong to no share
     ps = e["part_start"]
-    assert ps[0] == 0 and ps[-1] == len(items) and np.all(np.diff(ps) >= 1)
-    assert np.array_equal(items[:, F["part"]], np.repeat(np.arange(len(ps) - 1), np.diff(ps)))
+    n_pool = e["n_pool_items"]
+    assert ps[0] == 0 and ps[-1] + n_pool == len(items) and np.all(np.diff(ps) >= 1)
+    assert np.array_equal(items[: ps[-1], F["part"]], np.repeat(np.arange(len(ps) - 1), np.diff(ps)))
+    assert np.all(items[ps[-1] :, F["part"]] == len(ps) - 1) and np.all(items[ps[-1] :, F["n_branch"]] == 1)
+    pool_cap = kw.get("pool_item_tokens", 0) or 512
+    assert np.all(items[ps[-1] :, F["n_tokens"]] <= pool_cap)
     nsh = e["n_parts_shared"]
     assert np.all(items[: ps[nsh], F["kind"]] == 0) and np.all(items[ps[nsh] :, F["kind"]] == 1)
     rows = items[:, F["n_branch"]].astype(np.int64) * g * sh.n_kv_heads
@@ -157,13 +162,22 @@ def test_plan_integers_match_oracle(maker):
 
 
 @pytest.mark.parametrize("kw", [dict(share_prefix=False), dict(target_workgroups=8), dict(target_workgroups=100000),
-                                dict(max_branches_per_item=3)])
+                                dict(max_branches_per_item=3), dict(pool_pct=-1), dict(pool_pct=90, pool_item_tokens=64),
+                                dict(shared_cost_pct=300, shared_item_cost=5000, private_item_cost=1)])
 def test_plan_options(kw):
     reqs = [(37, [0]), (50, [0, 7, 16, 21]), (16, [1]), (700, [0, 33, 64, 65, 129, 300]), (1, [0]), (0, [45]),
             (333, list(range(30)))]
     e = check_plan_against_oracle(structure_custom(QWEN, reqs, seed=1), **kw)
     if kw.get("share_prefix") is False:
         assert e["n_parts_shared"] == 0
+    if kw.get("pool_pct") == -1:
+        assert e["n_pool_items"] == 0
+    if kw.get("pool_pct") == 90:
+        F = {n: i for i, n in enumerate(e["item_fields"])}
+        it = e["items"]
+        priv = it[it[:, F["kind"]] == 1]
+        pooled = it[e["part_start"][-1] :, F["n_tokens"]].sum()
+        assert 0.85 * priv[:, F["n_tokens"]].sum() <= pooled <= 0.9 * priv[:, F["n_tokens"]].sum() + 64
 
 
 def test_config4_plan_is_balanced():
