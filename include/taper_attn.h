@@ -132,8 +132,9 @@ typedef struct {
     int32_t max_branches_per_item; /* 0 = default (8 row tiles: 16 branches at 8 query heads per KV
                                       head); wider requests are cut into equal sub-groups of at
                                       most this size; at most 12 row tiles                     */
-    int32_t shared_cost_pct;   /* 0 = default (200): cost of a shared-prefix token relative to a
-                                  private one when cutting the work into equal shares          */
+    int32_t shared_cost_pct;   /* 0 = default (160 when no shared item is wider than 4 row tiles,
+                                  else 200): cost of a shared-prefix token relative to a private
+                                  one when cutting the work into equal shares                   */
     int32_t shared_item_cost;  /* 0 = default (800): fixed cost of a shared-prefix item, in private
                                   tokens' streaming time                                       */
     int32_t private_item_cost; /* 0 = default (128): fixed cost of a private item, same unit      */

@@ -112,11 +112,11 @@ DEV void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 // Log-sum-exp merge of all partials of (sequence s, kv head hk) -- its request's
 // prefix chunks and its own private chunks -- then normalisation and rounding to
 // bf16.  Threads idx0, idx0+stride, ... each own one float4 of the g x D result;
-// a thread works on U of them at once and takes the entries four at a time, so
-// that 4*U independent loads are in flight per round (the loads bypass the caches
+// a thread works on U of them at once and takes the entries R at a time, so
+// that R*U independent loads are in flight per round (the loads bypass the caches
 // and cost a full memory latency each).  Entries are taken in plan order, so the
 // result does not depend on which workgroup happens to run this.
-template <int D, int U>
+template <int D, int U, int R>
 DEV void merge_rows(const StepArgs& a, const int s, const int hk, const int idx0, const int stride) {
     const int g = a.gqa;
     const int total = g * (D / 4);
@@ -130,11 +130,11 @@ DEV void merge_rows(const StepArgs& a, const int s, const int hk, const int idx0
             L[u] = 0.f;
             acc[u] = (f32x4)(0.f);
         }
-        for (int e = e0; e < e1; e += 4) {
-            float2 ml[U][4];
-            f32x4 o[U][4];
+        for (int e = e0; e < e1; e += R) {
+            float2 ml[U][R];
+            f32x4 o[U][R];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
+            for (int k = 0; k < R; ++k) {
                 const bool have = e + k < e1;
                 const taper_merge_entry me = a.merge[have ? e + k : e];
 #pragma unroll
@@ -150,12 +150,14 @@ DEV void merge_rows(const StepArgs& a, const int s, const int hk, const int idx0
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const float mn = fmaxf(fmaxf(M[u], fmaxf(ml[u][0].x, ml[u][1].x)), fmaxf(ml[u][2].x, ml[u][3].x));
+                float mn = M[u];
+#pragma unroll
+                for (int k = 0; k < R; ++k) mn = fmaxf(mn, ml[u][k].x);
                 const float keep = fast_exp2(M[u] - mn);  // first round: exp2(-inf) = 0
                 L[u] *= keep;
                 acc[u] *= keep;
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
+                for (int k = 0; k < R; ++k) {
                     const float w = fast_exp2(ml[u][k].x - mn);
                     L[u] += w * ml[u][k].y;
                     acc[u] += w * o[u][k];
@@ -171,7 +173,9 @@ DEV void merge_rows(const StepArgs& a, const int s, const int hk, const int idx0
                 const int h = hk * g + j;
                 const f32x4 r = acc[u] * (1.0f / L[u]);
                 *(bf16x4*)((__bf16*)a.out + ((int64_t)s * a.n_q_heads + h) * D + 4 * d4) = __builtin_convertvector(r, bf16x4);
+#ifndef TAPER_WG_TRACE  // (trace builds use the lse buffer for their clocks)
                 if (a.lse && d4 == 0) a.lse[(int64_t)s * a.n_q_heads + h] = (M[u] + __log2f(L[u])) * 0.6931471805599453f;
+#endif
             }
         }
     }
@@ -324,7 +328,15 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
         __syncthreads();
         if (threadIdx.x == 0) sm.last = arrive_last(a, item.seq0, hk);
         __syncthreads();
-        if (sm.last) merge_rows<D, 1>(a, item.seq0, hk, threadIdx.x, 256);
+#ifdef TAPER_WG_TRACE
+        const long long t_m0 = wall_clock64();
+#endif
+        if (sm.last) merge_rows<D, 1, 8>(a, item.seq0, hk, threadIdx.x, 256);
+#ifdef TAPER_WG_TRACE
+        if (threadIdx.x == 0 && a.lse) {
+            ((long long*)a.lse)[4 * blockIdx.x + 3] += wall_clock64() - t_m0;
+        }
+#endif
     }
 }
 
@@ -425,7 +437,7 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
             for (int dt = 0; dt < DT; ++dt) O[k][dt] = (f32x4)(0.f);
         }
 
-        // Two register sets: while block b is computed from LDS, blocks b+1 and b+2 are in flight.
+        // Register sets for staging: while block b is computed from LDS, the next blocks are in flight.
         bf16x8 stgA[8], stgB[8];
         auto stage_load = [&](int b, bf16x8 (&stg)[8]) {
             if (stager && b < n_blocks) {
@@ -487,20 +499,47 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
             }
         };
 
-        stage_load(0, stgA);
-        stage_load(1, stgB);
-        stage_store(0, stgA);
-        __syncthreads();
-        for (int b = 0; b < n_blocks; b += 2) {
-            stage_load(b + 2, stgA);
-            compute(b, b & 1);
-            stage_store(b + 1, stgB);
+        if constexpr (NTW == 1) {
+            // registers to spare: a third set, so that three blocks are in flight while one is computed
+            // (a workgroup's share of a saturated memory system grows with what it keeps in flight)
+            bf16x8 stgC[8];
+            stage_load(0, stgA);
+            stage_load(1, stgB);
+            stage_load(2, stgC);
+            stage_store(0, stgA);
             __syncthreads();
-            if (b + 1 >= n_blocks) break;
-            stage_load(b + 3, stgB);
-            compute(b + 1, (b + 1) & 1);
-            stage_store(b + 2, stgA);
+            for (int b = 0; b < n_blocks; b += 3) {
+                stage_load(b + 3, stgA);
+                compute(b, b & 1);
+                stage_store(b + 1, stgB);
+                __syncthreads();
+                if (b + 1 >= n_blocks) break;
+                stage_load(b + 4, stgB);
+                compute(b + 1, (b + 1) & 1);
+                stage_store(b + 2, stgC);
+                __syncthreads();
+                if (b + 2 >= n_blocks) break;
+                stage_load(b + 5, stgC);
+                compute(b + 2, b & 1);
+                stage_store(b + 3, stgA);
+                __syncthreads();
+            }
+        } else {
+            stage_load(0, stgA);
+            stage_load(1, stgB);
+            stage_store(0, stgA);
             __syncthreads();
+            for (int b = 0; b < n_blocks; b += 2) {
+                stage_load(b + 2, stgA);
+                compute(b, b & 1);
+                stage_store(b + 1, stgB);
+                __syncthreads();
+                if (b + 1 >= n_blocks) break;
+                stage_load(b + 3, stgB);
+                compute(b + 1, (b + 1) & 1);
+                stage_store(b + 2, stgA);
+                __syncthreads();
+            }
         }
 
 #pragma unroll
@@ -521,8 +560,15 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
         __syncthreads();
         if (tid < item.n_branch) sm.last[tid] = arrive_last(a, item.seq0 + tid, hk);
         __syncthreads();
+#ifdef TAPER_WG_TRACE
+        const long long t_m0 = wall_clock64();
+#endif
         for (int b = wave; b < item.n_branch; b += 4)
-            if (sm.last[b]) merge_rows<D, 2>(a, item.seq0 + b, hk, lane, 64);
+            if (sm.last[b]) merge_rows<D, 2, 8>(a, item.seq0 + b, hk, lane, 64);
+#ifdef TAPER_WG_TRACE
+        __syncthreads();
+        if (tid == 0 && a.lse) ((long long*)a.lse)[4 * blockIdx.x + 3] += wall_clock64() - t_m0;
+#endif
         __syncthreads();
     }
 }
@@ -540,10 +586,9 @@ __global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void decode_kernel(StepArg
     __shared__ __attribute__((aligned(16))) char smem_raw[sizeof(Smem)];
     const int part = blockIdx.x / a.n_kv_heads;
     const int hk = blockIdx.x % a.n_kv_heads;
-#ifdef TAPER_WG_TRACE  // development builds only: per-workgroup clocks (start, own share done, left) into the lse buffer
+#ifdef TAPER_WG_TRACE  // development builds only: per-workgroup clocks (start, shared share done, left, time in merges) into the lse buffer
     long long* trace = (long long*)a.lse;
-    a.lse = nullptr;
-    if (threadIdx.x == 0) trace[3 * blockIdx.x] = wall_clock64();
+    if (threadIdx.x == 0) trace[4 * blockIdx.x] = wall_clock64();
 #endif
     int it0 = 0, it1 = 0;  // private items of this workgroup's share
     if (part < a.n_parts_shared) {
@@ -554,11 +599,11 @@ __global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void decode_kernel(StepArg
         it1 = a.part_start[part + 1];
     }
 #ifdef TAPER_WG_TRACE
-    if (threadIdx.x == 0) trace[3 * blockIdx.x + 1] = wall_clock64();  // shared share done / private share about to start
+    if (threadIdx.x == 0) trace[4 * blockIdx.x + 1] = wall_clock64();  // shared share done / private share about to start
 #endif
     private_items<D>(a, it0, it1, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
 #ifdef TAPER_WG_TRACE
-    if (threadIdx.x == 0) trace[3 * blockIdx.x + 2] = wall_clock64();
+    if (threadIdx.x == 0) trace[4 * blockIdx.x + 2] = wall_clock64();
 #endif
 }
 

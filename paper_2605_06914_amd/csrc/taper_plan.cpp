@@ -58,10 +58,11 @@ struct Cost {
 };
 
 // Cuts `segs` into workgroup shares of about `quota` cost units, at multiples of `blk` tokens
-// from each segment's start.  Appends items (tagged with part ids starting at part_id0) and
+// from each segment's start: shares are filled one after the other, a segment going on into the
+// next share where one is full.  Appends items (tagged with part ids starting at part_id0) and
 // returns the number of shares used.
-int partition(const std::vector<Segment>& segs, int64_t quota, int blk, const Cost cost, int part_id0,
-              std::vector<taper_work_item>* items) {
+int partition_fill(const std::vector<Segment>& segs, int64_t quota, int blk, const Cost cost, int part_id0,
+                   std::vector<taper_work_item>* items) {
     int64_t total_tokens = 0;
     for (const Segment& s : segs) total_tokens += s.n_tokens;
     if (total_tokens == 0) return 0;
@@ -101,6 +102,70 @@ int partition(const std::vector<Segment>& segs, int64_t quota, int blk, const Co
         }
     }
     return fill > 0 ? part + 1 : part;
+}
+
+// The same for items with a large fixed cost (shared-prefix items).  A segment that does not
+// fit what is left of the current share tops it up (if that is worth an item); what then
+// remains, if it is more than one share, is cut into equal items with a share each rather than
+// into full shares and a remainder (which would either be a short item paying the full fixed
+// cost or make the last item much longer than the others).  The last of those items is
+// `tail_discount` blocks shorter: the workgroup that finishes a shared prefix usually finds the
+// request's branches complete and has to merge them all.
+int partition_even(const std::vector<Segment>& segs, int64_t quota, int blk, const Cost cost, int64_t tail_discount,
+                   int part_id0, std::vector<taper_work_item>* items) {
+    quota = std::max<int64_t>(1, quota);
+    const int64_t blk_cost = std::max<int64_t>(1, blk * cost.per_token_pct / 100);
+    const int64_t min_blocks = std::max<int64_t>(1, (cost.fixed + blk_cost - 1) / blk_cost);
+    const int64_t cap = std::max<int64_t>(min_blocks, (quota - cost.fixed) / blk_cost);  // blocks of an item with a share to itself
+    int part = 0;
+    int64_t fill = 0;
+    auto emit = [&](const Segment& s, int64_t off, int64_t take) {
+        taper_work_item it;
+        std::memset(&it, 0, sizeof it);
+        it.seq0 = s.seq0;
+        it.n_branch = s.n_branch;
+        it.page0 = s.page0 + (int32_t)(off * blk / 16);
+        it.n_tokens = (int32_t)std::min<int64_t>(take * blk, s.n_tokens - off * blk);
+        it.kind = s.kind;
+        it.part = part_id0 + part;
+        items->push_back(it);
+        fill += cost.fixed + take * blk_cost;
+    };
+    auto close = [&]() {
+        if (fill > 0) ++part;
+        fill = 0;
+    };
+    for (const Segment& s : segs) {
+        int64_t remaining = (s.n_tokens + blk - 1) / blk, off = 0;  // blocks
+        int64_t room = (quota - fill - cost.fixed) / blk_cost;      // blocks that still fit the current share
+        if (fill > 0 && room < remaining && room < min_blocks) {    // not worth an item: start the next share
+            close();
+            room = cap;
+        }
+        if (remaining > room && fill > 0) {  // top the current share up
+            emit(s, 0, room);
+            close();
+            off = room;
+            remaining -= room;
+        }
+        if (remaining <= cap + min_blocks / 2) {  // one item; the next segment may top its share up
+            emit(s, off, remaining);
+            if (fill >= quota) close();
+            continue;
+        }
+        const int64_t spread = remaining + tail_discount;
+        const int64_t k = std::max<int64_t>(1, (spread + cap - 1) / cap);
+        for (int64_t i = 0; i < k; ++i) {
+            int64_t take = spread / k + (i < spread % k ? 1 : 0);
+            take = i + 1 < k ? std::max<int64_t>(1, std::min(take, remaining - (k - 1 - i))) : remaining;
+            emit(s, off, take);
+            close();
+            off += take;
+            remaining -= take;
+        }
+    }
+    close();
+    return part;
 }
 
 }  // namespace
@@ -240,9 +305,12 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
     // slice of a saturated memory system: its tokens are weighted by shared_cost_pct / 100.  Every
     // item also has a fixed cost (a shared item's is large: rows of several branches to store, and
     // the merges of all branches it completes).
-    const Cost cost_shared = {opts && opts->shared_cost_pct > 0 ? opts->shared_cost_pct : 200,
+    int widest = 0;  // row tiles of the widest shared item: up to 4, the kernel stages with three register sets
+    for (const Segment& s : shared) widest = std::max(widest, (s.n_branch * g + 15) / 16);
+    const Cost cost_shared = {opts && opts->shared_cost_pct > 0 ? opts->shared_cost_pct : (widest <= 4 ? 160 : 200),
                               opts && opts->shared_item_cost > 0 ? opts->shared_item_cost : 800};
     const Cost cost_priv = {100, opts && opts->private_item_cost > 0 ? opts->private_item_cost : 128};
+    const int64_t shared_tail_discount = 3;  // blocks: about what merging a request's branches costs
     int64_t cost_total = 0;
     for (const Segment& s : shared) {
         cost_total += cost_shared.fixed + (int64_t)s.n_tokens * cost_shared.per_token_pct / 100;
@@ -287,8 +355,8 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
     int64_t quota = std::max<int64_t>(kSharedBlockTokens, (cost_total + parts_total - 1) / parts_total);
     for (;;) {  // never more shares than asked for: an extra one would run after all the others
         p.items.clear();
-        p.n_parts_shared = partition(shared, quota, kSharedBlockTokens, cost_shared, 0, &p.items);
-        p.n_parts_private = partition(priv, quota, kPrivateBlockTokens, cost_priv, p.n_parts_shared, &p.items);
+        p.n_parts_shared = partition_even(shared, quota, kSharedBlockTokens, cost_shared, shared_tail_discount, 0, &p.items);
+        p.n_parts_private = partition_fill(priv, quota, kPrivateBlockTokens, cost_priv, p.n_parts_shared, &p.items);
         if (p.n_parts_shared + p.n_parts_private <= parts_total || quota >= cost_total * 2 + 4096) break;
         quota += std::max<int64_t>(16, quota / 256);
     }
