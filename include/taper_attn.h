@@ -141,8 +141,9 @@ typedef struct {
     int32_t pool_pct;          /* 0 = default (25 when the step has shared-prefix work, else none):
                                   percentage of the private tokens that no share owns; workgroups
                                   that finish their share take them, an item at a time, so the
-                                  launch ends evenly.  -1 = none                                 */
-    int32_t pool_item_tokens;  /* 0 = default (512): size of the pool's items                     */
+                                  launch ends evenly.  -1 = none; values above 90 count as 90    */
+    int32_t pool_item_tokens;  /* 0 = default (512): size of the pool's items, rounded down to a
+                                  multiple of 32 tokens (at least 32)                            */
 } taper_plan_options;
 
 TAPER_API int taper_create(const taper_attn_config *cfg /* host */, taper_ctx **out_ctx);

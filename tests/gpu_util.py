@@ -54,8 +54,13 @@ def assert_parity(got, ref, what=""):
     assert mx <= MAX_ABS, f"{what}: max-abs {mx} > {MAX_ABS}"
     assert mean <= MEAN_ABS, f"{what}: mean-abs {mean} > {MEAN_ABS}"
     # the absolute bar is loose for long contexts (outputs shrink like 1/sqrt(n)); bf16 rounding of the
-    # output alone is 2^-9 relative per element, so hold the error to a few percent of the output scale too
-    assert mx <= 0.05 * rms + 1e-6, f"{what}: max-abs {mx} is more than 5% of rms(ref) {rms}"
+    # output alone is 2^-9 relative per element, so hold each sequence's error to a few percent of that
+    # sequence's own output scale too
+    ax = tuple(range(1, ref.ndim))
+    rms_s = np.sqrt(np.mean(ref ** 2, axis=ax))
+    rel = err.max(axis=ax) / (rms_s + 1e-12)
+    worst = int(np.argmax(rel))
+    assert rel[worst] <= 0.05, f"{what}: sequence {worst}: max-abs {err[worst].max()} is more than 5% of its rms {rms_s[worst]}"
     return mx, mean
 
 

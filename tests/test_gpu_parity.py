@@ -132,6 +132,50 @@ def test_run_to_run_bit_identical(ctx_qwen):
     assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
 
 
+POOL_REQS = [(2100, [0]), (900, [0]), (1500, [5, 60, 0, 17, 130, 40, 3, 3, 250]), (640, [700, 1, 33]), (77, [0]),
+             (3000, [0]), (16, [1]), (1200, [12] * 20)]
+
+
+@pytest.mark.parametrize("kw", [dict(pool_pct=-1), dict(pool_pct=90, pool_item_tokens=64), dict(pool_pct=50),
+                                dict(pool_pct=25, target_workgroups=64),
+                                dict(shared_cost_pct=300, shared_item_cost=5000, private_item_cost=1),
+                                dict(max_branches_per_item=3), dict(max_branches_per_item=24),
+                                dict(max_branches_per_item=8, pool_pct=75, pool_item_tokens=200)])
+def test_plan_options_do_not_change_the_result(ctx_qwen, kw):
+    """The unowned pool of private items (claimed at run time by workgroups that
+    finish early), the cost weights and the branch cap only move work between
+    workgroups; every setting must meet the same parity bar."""
+    b = fill_values_numpy(structure_custom(QWEN, POOL_REQS, seed=107))
+    ref, ref_lse = run_oracle(b)
+    got, lse, _ = run_gpu(ctx_qwen, b, **kw)
+    assert_parity(got, ref, f"options {kw}")
+    assert np.max(np.abs(lse - ref_lse)) <= 2e-3
+
+
+def test_same_plan_replayed(ctx_qwen):
+    """The arrival counters and the pool's claim counter reset themselves inside the
+    kernel: replaying one plan must give the same bits every time."""
+    import torch
+
+    b = fill_values_numpy(structure_custom(QWEN, POOL_REQS, seed=108))
+    st = b.structure
+    q, kv = torch_bf16(b.q), torch_bf16(b.kv)
+    plan = ctx_qwen.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages,
+                               pool_pct=60, pool_item_tokens=128)
+    assert plan.export()["n_pool_items"] > 0
+    bits = []
+    for _ in range(6):
+        out = torch.full_like(q, float("nan"))
+        ctx_qwen.decode_step_attention(plan, q, kv, out)
+        torch.cuda.synchronize()
+        bits.append(bits_from_torch(out))
+    plan.free()
+    ref, _ = run_oracle(b)
+    assert_parity(f32_from_bf16_bits(bits[0]).astype(np.float64), ref, "replayed plan")
+    for x in bits[1:]:
+        assert np.array_equal(bits[0], x)
+
+
 def test_sibling_independence(ctx_qwen):
     """Lemma 1: which siblings share the step must not change a branch's output
     (beyond summation order; the prefix partial is computed per row, so it is in

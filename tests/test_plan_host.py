@@ -139,7 +139,7 @@ def check_plan_against_oracle(st, **kw):
     assert ps[0] == 0 and ps[-1] + n_pool == len(items) and np.all(np.diff(ps) >= 1)
     assert np.array_equal(items[: ps[-1], F["part"]], np.repeat(np.arange(len(ps) - 1), np.diff(ps)))
     assert np.all(items[ps[-1] :, F["part"]] == len(ps) - 1) and np.all(items[ps[-1] :, F["n_branch"]] == 1)
-    pool_cap = kw.get("pool_item_tokens", 0) or 512
+    pool_cap = max(32, (kw.get("pool_item_tokens", 0) or 512) // 32 * 32)
     assert np.all(items[ps[-1] :, F["n_tokens"]] <= pool_cap)
     nsh = e["n_parts_shared"]
     assert np.all(items[: ps[nsh], F["kind"]] == 0) and np.all(items[ps[nsh] :, F["kind"]] == 1)
@@ -162,7 +162,7 @@ def test_plan_integers_match_oracle(maker):
 
 
 @pytest.mark.parametrize("kw", [dict(share_prefix=False), dict(target_workgroups=8), dict(target_workgroups=100000),
-                                dict(max_branches_per_item=3), dict(pool_pct=-1), dict(pool_pct=90, pool_item_tokens=64),
+                                dict(max_branches_per_item=3), dict(pool_pct=-1), dict(pool_pct=90, pool_item_tokens=64), dict(pool_pct=100, pool_item_tokens=200),
                                 dict(shared_cost_pct=300, shared_item_cost=5000, private_item_cost=1)])
 def test_plan_options(kw):
     reqs = [(37, [0]), (50, [0, 7, 16, 21]), (16, [1]), (700, [0, 33, 64, 65, 129, 300]), (1, [0]), (0, [45]),
