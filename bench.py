@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--shared-cost-pct", type=int, default=0)
     ap.add_argument("--no-share", action="store_true", help="every branch streams its prefix itself (for comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--kernel-iters", type=int, default=20)
+    ap.add_argument("--kernel-iters", type=int, default=50)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times: scales the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--sweep-pools", type=int, default=16, help="distinct KV pools the 64 layers of the sweep cycle through")
@@ -107,8 +107,13 @@ def run_sweep(args):
                      "tokens_unique": st.unique_tokens, "ms_per_step": round(ms, 3), "gbps_unique": round(gbps, 1),
                      "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)})
     t_base = rows[0]["ms_per_step"]
-    for r in rows:
+    for r, st in zip(rows, sts.values()):
         r["externality_ms"] = round(r["ms_per_step"] - t_base, 3)
+        if r["k"]:
+            # marginal cost of one admitted branch per layer, beside the bytes it adds (its private suffix:
+            # the prefix is already streamed for the protected branch)
+            r["externality_us_per_branch_layer"] = round((r["ms_per_step"] - t_base) * 1e3 / (32 * r["k"]) / n_layers, 4)
+            r["kv_bytes_added_per_branch_layer"] = int((st.kv_bytes_unique - sts[0].kv_bytes_unique) / (32 * r["k"]))
     ctx.close()
     return rows, n_layers, sh
 
@@ -198,18 +203,32 @@ def main():
     kt = {"decode_us": 0.0, "decode_us_min": 0.0}
     n_kt = min(n_layers, 8)
     for l in range(n_kt):
-        r = ctx.kernel_times(plan, qs[l], kvs[l], outs[l], warmup=2, iters=args.kernel_iters)
+        r = ctx.kernel_times(plan, qs[l], kvs[l], outs[l], warmup=10, iters=args.kernel_iters)
         for k in kt:
             kt[k] += r[k] / n_kt
     probe = ctx.step_latency_probe(plan, qs, kvs, outs, warmup=2, iters=max(5, args.steps))
-    # the dominant kernel streams every KV token the plan lists, once (a shared prefix once per item)
-    dom_bytes = (tok_shared + tok_private) * sh.kv_bytes_per_token
+    # algorithmic bytes of one launch: every unique KV token once (a shared prefix once per request) plus
+    # q read and out written; the plan may list a prefix more than once (requests wider than one
+    # workgroup's row tiles are cut into sub-groups), which is reported beside it, not counted
+    dom_bytes = st.kv_bytes_unique + st.qo_bytes
     achieved = dom_bytes / (kt["decode_us"] * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                "bytes_per_launch": dom_bytes, "avg_launch_us": round(kt["decode_us"], 2),
+                "bytes_per_launch": dom_bytes, "kv_bytes_listed_by_plan": (tok_shared + tok_private) * sh.kv_bytes_per_token,
+                "avg_launch_us": round(kt["decode_us"], 2),
                 "kernel_us": {k: round(v, 2) for k, v in kt.items()},
-                "workgroups": (e["n_parts_shared"] + e["n_parts_private"]) * sh.n_kv_heads}
+                "workgroups": (e["n_parts_shared"] + e["n_parts_private"]) * sh.n_kv_heads,
+                "pool_items": e["n_pool_items"]}
+
+    # HBM bytes per launch as the profiler's counters saw them (a stored profile of this kernel and workload,
+    # see profiles/; counters cannot be read from inside this process)
+    tf = os.path.join(ROOT, "profiles", "decode_kernel_traffic.json")
+    if os.path.exists(tf) and not args.no_share and not args.target_workgroups and not args.shared_cost_pct:
+        t = json.load(open(tf)).get(args.workload)
+        if t:
+            roofline["traffic"] = t["fetch_bytes"] + t["write_bytes"]
+            roofline["traffic_detail"] = {"fetch_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
+                                          "source": "profiles/decode_kernel_%s.md" % args.workload}
 
     # ---- CPU oracle on a bounded sample of the same workload (rank 0, N=1)
     cpu = None
