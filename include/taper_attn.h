@@ -96,7 +96,7 @@ typedef struct {
                           = part_base + hk * n_branch * gqa + b * gqa + j           */
     int32_t kind;      /* 0 = shared prefix of a parallel request, 1 = private      */
     int32_t part;      /* workgroup share this item belongs to; n_parts for pool items */
-    int32_t reserved;
+    int32_t merge0;    /* merge_start[seq0]: where the merge entries of the item's sequences begin */
 } taper_work_item;
 
 /* Where sequence s finds one of its partials: rows first_row + hk*rows_per_head + j */

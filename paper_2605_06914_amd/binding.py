@@ -33,7 +33,7 @@ class taper_attn_config(ctypes.Structure):
 
 class taper_work_item(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("seq0", "n_branch", "page0", "n_tokens", "part_base", "kind", "part", "reserved")]
+                ("seq0", "n_branch", "page0", "n_tokens", "part_base", "kind", "part", "merge0")]
 
 
 class taper_merge_entry(ctypes.Structure):

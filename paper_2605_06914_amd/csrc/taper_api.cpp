@@ -162,6 +162,7 @@ taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const vo
     a.ws_o = (float*)((char*)ctx->ws + ws_o_offset(ctx));
     a.bt_stride = plan->host.bt_stride;
     a.n_seqs = plan->host.n_seqs;
+    a.n_merge = (int32_t)plan->host.merge.size();
     a.n_q_heads = ctx->cfg.n_q_heads;
     a.n_kv_heads = ctx->cfg.n_kv_heads;
     a.gqa = ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads;

@@ -29,6 +29,7 @@ struct StepArgs {
     int32_t pool_first, n_pool_items;  // the pool: items [pool_first, pool_first + n_pool_items)
     int32_t bt_stride;
     int32_t n_seqs;
+    int32_t n_merge;           // entries in `merge`
     int32_t n_q_heads, n_kv_heads, gqa, head_dim;
     int32_t n_parts_shared, n_parts_private;
     int32_t max_row_tiles_shared;

@@ -109,84 +109,122 @@ DEV f32x4 coherent_load4(const float* p) {
 // before the arrival counter's increment for a reader on another compute unit.)
 DEV void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// What the end of an item needs from the plan, fetched when the item starts so that no
+// dependent load is left for the end, where each one costs a loaded memory latency:
+// merge_start[seq0 + b] for the item's sequences and the first kMetaWindow merge entries from
+// merge_start[seq0] on (the sequences' entry lists are adjacent).
+constexpr int kMetaWindow = 128;
+struct MergeMeta {
+    int ms[65];
+    taper_merge_entry me[kMetaWindow];
+};
+struct MetaRegs {
+    int ms;
+    taper_merge_entry me;
+};
+// A per-lane value the compiler must not reason about: whatever is derived from it is
+// computed where it is used instead of being hoisted out of the item loop, where it would
+// sit in registers (or, worse, in scratch) for the whole kernel.
+DEV int opaque(int v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+DEV MetaRegs meta_load(const StepArgs& a, const taper_work_item& item, const int tid_) {
+    const int tid = opaque(tid_);
+    MetaRegs r;
+    r.ms = 0;
+    r.me.first_row = 0;
+    r.me.rows_per_head = 0;
+    if (tid <= item.n_branch) r.ms = a.merge_start[item.seq0 + tid];
+    if (tid < kMetaWindow && item.merge0 + tid < a.n_merge) r.me = a.merge[item.merge0 + tid];
+    return r;
+}
+DEV void meta_store(MergeMeta& mm, const MetaRegs& r, const int n_branch, const int tid_) {
+    const int tid = opaque(tid_);
+    if (tid <= n_branch) mm.ms[tid] = r.ms;
+    if (tid < kMetaWindow) mm.me[tid] = r.me;
+}
+DEV taper_merge_entry merge_entry(const StepArgs& a, const MergeMeta& mm, const int e) {
+    const int t = e - mm.ms[0];
+    if (t < kMetaWindow) return mm.me[t];
+    return a.merge[e];
+}
+
 // Log-sum-exp merge of all partials of (sequence s, kv head hk) -- its request's
-// prefix chunks and its own private chunks -- then normalisation and rounding to
-// bf16.  Threads idx0, idx0+stride, ... each own one float4 of the g x D result;
-// a thread works on U of them at once and takes the entries R at a time, so
-// that R*U independent loads are in flight per round (the loads bypass the caches
-// and cost a full memory latency each).  Entries are taken in plan order, so the
-// result does not depend on which workgroup happens to run this.
+// prefix chunks and its own private chunks, entries [e0, e1) of the merge map -- then
+// normalisation and rounding to bf16.  Entries are taken in plan order, so the result
+// does not depend on which workgroup happens to run this.  The loads bypass the caches
+// and cost a full memory latency per round, so a round keeps R entries in flight.
+//
+// Thread idx (of n_thr) owns float4 columns c, c + LPR, ... (U of them) of one row, where
+// LPR = D/4/U lanes cover a row; n_thr / LPR rows are merged per pass.
 template <int D, int U, int R>
-DEV void merge_rows(const StepArgs& a, const int s, const int hk, const int idx0, const int stride) {
+DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const int hk, const int e0, const int e1,
+                    const int idx_, const int n_thr) {
+    constexpr int LPR = D / 4 / U;
     const int g = a.gqa;
-    const int total = g * (D / 4);
-    const int e0 = a.merge_start[s], e1 = a.merge_start[s + 1];
-    for (int base = idx0; base < total; base += stride * U) {
-        float M[U], L[U];
+    const int idx = opaque(idx_);
+    const int jr = idx / LPR, c0 = idx % LPR;
+    for (int j0 = 0; j0 < g; j0 += n_thr / LPR) {
+        const int j = j0 + jr;
+        const bool okr = j < g;
+        float M = -INFINITY, L = 0.f;
         f32x4 acc[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            M[u] = -INFINITY;
-            L[u] = 0.f;
-            acc[u] = (f32x4)(0.f);
-        }
+        for (int u = 0; u < U; ++u) acc[u] = (f32x4)(0.f);
         for (int e = e0; e < e1; e += R) {
-            float2 ml[U][R];
-            f32x4 o[U][R];
+            float2 ml[R];
+            f32x4 o[R][U];
 #pragma unroll
             for (int k = 0; k < R; ++k) {
-                const bool have = e + k < e1;
-                const taper_merge_entry me = a.merge[have ? e + k : e];
+                ml[k] = make_float2(-INFINITY, 0.f);
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int idx = base + u * stride;
-                    const bool ok = have && idx < total;
-                    const int j = ok ? idx / (D / 4) : 0, d4 = ok ? idx % (D / 4) : 0;
-                    const int64_t rowi = (int64_t)me.first_row + (int64_t)hk * me.rows_per_head + j;
-                    ml[u][k] = coherent_load2((const float*)(a.ws_ml + rowi));
-                    o[u][k] = coherent_load4(a.ws_o + rowi * D + 4 * d4);
-                    if (!ok) ml[u][k] = make_float2(-INFINITY, 0.f);
+                for (int u = 0; u < U; ++u) o[k][u] = (f32x4)(0.f);
+                if (e + k < e1) {
+                    const taper_merge_entry me = merge_entry(a, mm, e + k);
+                    const int64_t rowi = (int64_t)me.first_row + (int64_t)hk * me.rows_per_head + (okr ? j : 0);
+                    const float2 v = coherent_load2((const float*)(a.ws_ml + rowi));
+                    if (okr) ml[k] = v;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) o[k][u] = coherent_load4(a.ws_o + rowi * D + 4 * (c0 + LPR * u));
                 }
             }
+            float mn = M;
+#pragma unroll
+            for (int k = 0; k < R; ++k) mn = fmaxf(mn, ml[k].x);
+            const float keep = fast_exp2(M - mn);  // first round: exp2(-inf) = 0
+            L *= keep;
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[u] *= keep;
+#pragma unroll
+            for (int k = 0; k < R; ++k) {
+                const float w = fast_exp2(ml[k].x - mn);
+                L += w * ml[k].y;
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[u] += w * o[k][u];
+            }
+            M = mn;
+        }
+        if (okr) {
+            const int h = hk * g + j;
+            const float inv = 1.0f / L;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                float mn = M[u];
-#pragma unroll
-                for (int k = 0; k < R; ++k) mn = fmaxf(mn, ml[u][k].x);
-                const float keep = fast_exp2(M[u] - mn);  // first round: exp2(-inf) = 0
-                L[u] *= keep;
-                acc[u] *= keep;
-#pragma unroll
-                for (int k = 0; k < R; ++k) {
-                    const float w = fast_exp2(ml[u][k].x - mn);
-                    L[u] += w * ml[u][k].y;
-                    acc[u] += w * o[u][k];
-                }
-                M[u] = mn;
+                const f32x4 r = acc[u] * inv;
+                *(bf16x4*)((__bf16*)a.out + ((int64_t)s * a.n_q_heads + h) * D + 4 * (c0 + LPR * u)) = __builtin_convertvector(r, bf16x4);
             }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int idx = base + u * stride;
-            if (idx < total) {
-                const int j = idx / (D / 4), d4 = idx % (D / 4);
-                const int h = hk * g + j;
-                const f32x4 r = acc[u] * (1.0f / L[u]);
-                *(bf16x4*)((__bf16*)a.out + ((int64_t)s * a.n_q_heads + h) * D + 4 * d4) = __builtin_convertvector(r, bf16x4);
 #ifndef TAPER_WG_TRACE  // (trace builds use the lse buffer for their clocks)
-                if (a.lse && d4 == 0) a.lse[(int64_t)s * a.n_q_heads + h] = (M[u] + __log2f(L[u])) * 0.6931471805599453f;
+            if (a.lse && c0 == 0) a.lse[(int64_t)s * a.n_q_heads + h] = (M + __log2f(L)) * 0.6931471805599453f;
 #endif
-            }
         }
     }
 }
 
-// A workgroup that has written a partial of (sequence s, kv head hk) announces it.
-// Returns true to the one caller that arrives last: every other partial of that
-// (s, hk) has then been written through (each writer waited for its stores before
+// A workgroup that has written a partial of (sequence s, kv head hk), one of n_entries,
+// announces it.  Returns true to the one caller that arrives last: every other partial of
+// that (s, hk) has then been written through (each writer waited for its stores before
 // its increment) and the caller must merge.  The counter is left at zero for the next launch.
-DEV bool arrive_last(const StepArgs& a, const int s, const int hk) {
-    const int n_entries = a.merge_start[s + 1] - a.merge_start[s];
+DEV bool arrive_last(const StepArgs& a, const int s, const int hk, const int n_entries) {
     int* c = a.counters + (int64_t)s * a.n_kv_heads + hk;
     const bool last = atomicAdd(c, 1) == n_entries - 1;
     if (last) *c = 0;
@@ -211,6 +249,7 @@ struct PrivateSmem {
     float2 ml[4][16];
     int last;
     int pick;  // pool item a workgroup has taken
+    MergeMeta meta;
 };
 
 // One private item: a chunk of one sequence's own tokens, for kv head hk.
@@ -233,6 +272,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
         const int n_tok = item.n_tokens;
         const int n_pages = (n_tok + 15) >> 4;
         const int n_blocks = (n_tok + 31) >> 5;
+        const MetaRegs mr = meta_load(a, item, threadIdx.x);
 
         bf16x8 qf[KS];
         {
@@ -303,6 +343,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
             for (int dt = 0; dt < DT; ++dt) *(f32x4*)&sm_o[wave][n][16 * dt + 4 * qd] = O[dt];
         }
         __syncthreads();
+        meta_store(sm.meta, mr, 1, threadIdx.x);  // (after the barrier: nobody still merges the previous item)
         for (int idx = threadIdx.x; idx < g * (D / 4); idx += 256) {
             const int r = idx / (D / 4), d4 = idx % (D / 4);
             float mw[4], M = -INFINITY;
@@ -326,12 +367,12 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
         // publish the partial; whoever completes the sequence's set merges it
         stores_done();
         __syncthreads();
-        if (threadIdx.x == 0) sm.last = arrive_last(a, item.seq0, hk);
+        if (threadIdx.x == 0) sm.last = arrive_last(a, item.seq0, hk, sm.meta.ms[1] - sm.meta.ms[0]);
         __syncthreads();
 #ifdef TAPER_WG_TRACE
         const long long t_m0 = wall_clock64();
 #endif
-        if (sm.last) merge_rows<D, 1, 8>(a, item.seq0, hk, threadIdx.x, 256);
+        if (sm.last) merge_rows<D, 1, 8>(a, sm.meta, item.seq0, hk, sm.meta.ms[0], sm.meta.ms[1], threadIdx.x, 256);
 #ifdef TAPER_WG_TRACE
         if (threadIdx.x == 0 && a.lse) {
             ((long long*)a.lse)[4 * blockIdx.x + 3] += wall_clock64() - t_m0;
@@ -382,6 +423,7 @@ struct SharedSmem {
     static constexpr int BUF = 4 * PAGE_LDS;  // 4 pages = 64 tokens
     __bf16 kv[2 * BUF];
     int last[64];  // per branch of the current item
+    MergeMeta meta;
 };
 
 template <int D, int NTW>
@@ -415,6 +457,7 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
         const int tiles = (R + 15) >> 4;
         int n_act = (tiles - wave + 3) >> 2;       // tiles wave, wave+4, ...
         n_act = n_act < 0 ? 0 : (n_act > NTW ? NTW : n_act);
+        meta_store(sm.meta, meta_load(a, item, tid), item.n_branch, tid);
 
         bf16x8 qf[NTW][KS];
         float m[NTW], l[NTW];
@@ -558,13 +601,13 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
         // publish the partials; for every branch whose set is now complete, merge (one wave per branch)
         stores_done();
         __syncthreads();
-        if (tid < item.n_branch) sm.last[tid] = arrive_last(a, item.seq0 + tid, hk);
+        if (tid < item.n_branch) sm.last[tid] = arrive_last(a, item.seq0 + tid, hk, sm.meta.ms[tid + 1] - sm.meta.ms[tid]);
         __syncthreads();
 #ifdef TAPER_WG_TRACE
         const long long t_m0 = wall_clock64();
 #endif
         for (int b = wave; b < item.n_branch; b += 4)
-            if (sm.last[b]) merge_rows<D, 2, 8>(a, item.seq0 + b, hk, lane, 64);
+            if (sm.last[b]) merge_rows<D, D / 32, 5>(a, sm.meta, item.seq0 + b, hk, sm.meta.ms[b], sm.meta.ms[b + 1], lane, 64);
 #ifdef TAPER_WG_TRACE
         __syncthreads();
         if (tid == 0 && a.lse) ((long long*)a.lse)[4 * blockIdx.x + 3] += wall_clock64() - t_m0;

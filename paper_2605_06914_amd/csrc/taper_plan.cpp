@@ -401,6 +401,7 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
         p.merge_start[s + 1] = p.merge_start[s] + (int32_t)per_seq[s].size();
         p.merge.insert(p.merge.end(), per_seq[s].begin(), per_seq[s].end());
     }
+    for (taper_work_item& it : p.items) it.merge0 = p.merge_start[it.seq0];
     return TAPER_OK;
 }
 
