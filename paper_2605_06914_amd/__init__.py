@@ -9,6 +9,11 @@ from .binding import (  # noqa: F401
     EXPORTED,
     LIB_PATH,
     Plan,
+    Window,
+    admit_step,
+    predictor_eval,
+    predictor_fit,
+    predictor_mape,
     TaperError,
     load_library,
     taper_plan_options,

@@ -23,6 +23,8 @@ EXPORTED = [
     "taper_plan_resolve_slots_host", "taper_plan_resolve_slots", "taper_decode_step_attention",
     "taper_decode_step_attention_simple", "taper_step_latency_probe", "taper_kernel_times",
     "taper_strerror", "taper_last_error",
+    "taper_predictor_fit", "taper_predictor_eval", "taper_predictor_mape", "taper_window_create",
+    "taper_window_destroy", "taper_window_push", "taper_window_size", "taper_window_fit", "taper_admit_step",
 ]
 
 
@@ -68,6 +70,23 @@ class taper_probe_result(ctypes.Structure):
                 ("gbps_unique", ctypes.c_double), ("gbps_logical", ctypes.c_double)]
 
 
+class taper_predictor(ctypes.Structure):
+    _fields_ = [("a", ctypes.c_double), ("b", ctypes.c_double), ("c", ctypes.c_double)]
+
+
+class taper_admission_options(ctypes.Structure):
+    _fields_ = [("rho", ctypes.c_double), ("utility_kind", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class taper_admission_result(ctypes.Structure):
+    _fields_ = [("t0_ms", ctypes.c_double), ("budget_ms", ctypes.c_double), ("t_pred_ms", ctypes.c_double),
+                ("n_tokens", ctypes.c_int64), ("l_context", ctypes.c_int64), ("evaluations", ctypes.c_int64),
+                ("admitted", ctypes.c_int64)]
+
+
+UTILITY_KINDS = {"linear": 0, "concave": 1, "table": 2}
+
+
 class TaperError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"taper_attn status {status}: {message}")
@@ -106,6 +125,21 @@ def load_library() -> ctypes.CDLL:
     lib.taper_step_latency_probe.argtypes = [vp, vp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                              ci, ci, vp, ctypes.POINTER(taper_probe_result)]
     lib.taper_kernel_times.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
+    dp, f64 = ctypes.POINTER(ctypes.c_double), ctypes.c_double
+    pp = ctypes.POINTER(taper_predictor)
+    lib.taper_predictor_fit.argtypes = [i64, vp, vp, vp, pp, dp]
+    lib.taper_predictor_eval.argtypes = [pp, f64, f64]
+    lib.taper_predictor_eval.restype = f64
+    lib.taper_predictor_mape.argtypes = [pp, i64, vp, vp, vp, dp]
+    lib.taper_window_create.argtypes = [ctypes.c_int32, ctypes.POINTER(vp)]
+    lib.taper_window_destroy.argtypes = [vp]
+    lib.taper_window_destroy.restype = None
+    lib.taper_window_push.argtypes = [vp, f64, f64, f64]
+    lib.taper_window_size.argtypes = [vp]
+    lib.taper_window_size.restype = ctypes.c_int32
+    lib.taper_window_fit.argtypes = [vp, pp, dp]
+    lib.taper_admit_step.argtypes = [pp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, ctypes.POINTER(taper_admission_options),
+                                     vp, ctypes.POINTER(taper_admission_result)]
     lib.taper_strerror.argtypes = [ci]
     lib.taper_strerror.restype = ctypes.c_char_p
     lib.taper_last_error.restype = ctypes.c_char_p
@@ -253,3 +287,90 @@ class Context:
         _check(load_library().taper_kernel_times(self._h, plan._h, _ptr(q), _ptr(kv_pages), _ptr(out), warmup, iters,
                                                  _stream(stream), us))
         return dict(decode_us=us[0], decode_us_min=us[1])
+
+
+# ----------------------------------------------------------------------------- controller side (host only)
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def predictor_fit(n_tokens, l_context, t_ms):
+    """(a, b, c) of T = a + b n_tokens + c L_context by least squares, and the fit's MAPE in percent."""
+    lib = load_library()
+    n, L, t = _f64(n_tokens), _f64(l_context), _f64(t_ms)
+    if not (n.shape == L.shape == t.shape and n.ndim == 1):
+        raise ValueError("n_tokens, l_context, t_ms must be 1-D arrays of one length")
+    p, m = taper_predictor(), ctypes.c_double()
+    _check(lib.taper_predictor_fit(len(n), n.ctypes.data, L.ctypes.data, t.ctypes.data, ctypes.byref(p), ctypes.byref(m)))
+    return (p.a, p.b, p.c), m.value
+
+
+def predictor_eval(coef, n_tokens, l_context) -> float:
+    return load_library().taper_predictor_eval(ctypes.byref(taper_predictor(*coef)), float(n_tokens), float(l_context))
+
+
+def predictor_mape(coef, n_tokens, l_context, t_ms) -> float:
+    lib = load_library()
+    n, L, t = _f64(n_tokens), _f64(l_context), _f64(t_ms)
+    m = ctypes.c_double()
+    _check(lib.taper_predictor_mape(ctypes.byref(taper_predictor(*coef)), len(n), n.ctypes.data, L.ctypes.data,
+                                    t.ctypes.data, ctypes.byref(m)))
+    return m.value
+
+
+class Window:
+    """The most recent `capacity` observed steps; fit() refreshes the predictor from them."""
+
+    def __init__(self, capacity: int = 200):
+        self._lib = load_library()
+        h = ctypes.c_void_p()
+        _check(self._lib.taper_window_create(capacity, ctypes.byref(h)))
+        self._h = h
+
+    def push(self, n_tokens, l_context, t_ms):
+        _check(self._lib.taper_window_push(self._h, float(n_tokens), float(l_context), float(t_ms)))
+
+    def __len__(self):
+        return self._lib.taper_window_size(self._h)
+
+    def fit(self):
+        p, m = taper_predictor(), ctypes.c_double()
+        _check(self._lib.taper_window_fit(self._h, ctypes.byref(p), ctypes.byref(m)))
+        return (p.a, p.b, p.c), m.value
+
+    def close(self):
+        if self._h:
+            self._lib.taper_window_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def admit_step(coef, base_context, slack_ms, branch_context, rho=1.0, utility="linear", weight=None, utility_table=None):
+    """One planner invocation.  branch_context: per request, the context lengths of its ready branches in
+    admission order.  utility_table (for utility="table"): per request u(0..ready).  Returns (granted, result dict)."""
+    lib = load_library()
+    R = len(base_context)
+    base = np.ascontiguousarray(base_context, dtype=np.int64)
+    slack = _f64(slack_ms)
+    start = np.zeros(R + 1, np.int32)
+    start[1:] = np.cumsum([len(b) for b in branch_context])
+    flat = np.ascontiguousarray([c for b in branch_context for c in b], dtype=np.int64)
+    w = _f64(weight) if weight is not None else None
+    tab = _f64([u for t in utility_table for u in t]) if utility_table is not None else None
+    if tab is not None and len(tab) != int(start[-1]) + R:
+        raise ValueError("utility_table needs ready + 1 entries per request")
+    if len(slack) != R or len(branch_context) != R or (w is not None and len(w) != R):
+        raise ValueError("per-request arrays differ in length")
+    granted = np.zeros(R, np.int32)
+    opts = taper_admission_options(float(rho), UTILITY_KINDS[utility], 0)
+    res = taper_admission_result()
+    _check(lib.taper_admit_step(ctypes.byref(taper_predictor(*coef)), R, base.ctypes.data, slack.ctypes.data,
+                                start.ctypes.data, flat.ctypes.data if len(flat) else None,
+                                w.ctypes.data if w is not None else None, tab.ctypes.data if tab is not None else None,
+                                ctypes.byref(opts), granted.ctypes.data, ctypes.byref(res)))
+    return granted, {f[0]: getattr(res, f[0]) for f in taper_admission_result._fields_}

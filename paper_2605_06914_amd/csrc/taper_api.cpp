@@ -33,6 +33,10 @@ int fail_hip(hipError_t e, const char* what) {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 }  // namespace
 
+namespace taper {
+int set_error(int code, const std::string& msg) { return fail(code, msg); }
+}  // namespace taper
+
 // Device + pinned-host buffers of a plan.  They are recycled through the context
 // so that a steady-state decode loop neither allocates nor frees (hipFree would
 // synchronise the device once per step).

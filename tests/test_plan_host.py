@@ -20,7 +20,7 @@ QWEN = AttnShape(64, 8, 128, 16)
 
 def test_library_exports_every_declared_symbol():
     lib = load_library()
-    header = open(os.path.join(ROOT, "include", "taper_attn.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include"))))
     declared = set(re.findall(r"TAPER_API\s+[\w\s\*]+?\b(taper_\w+)\s*\(", header))
     assert declared == set(EXPORTED), declared ^ set(EXPORTED)
     for name in declared:
