@@ -22,4 +22,5 @@ from .generators import (  # noqa: F401
     structure_config4,
     structure_config5,
     structure_custom,
+    subset_rows,
 )

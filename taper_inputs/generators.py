@@ -272,6 +272,18 @@ def fill_values_numpy(st: BatchStructure, seed: Optional[int] = None, chunk_page
     return Batch(st, q, kv)
 
 
+def subset_rows(st: BatchStructure, seq_ids: Sequence[int]) -> BatchStructure:
+    """The sequences ``seq_ids`` (ascending) over the SAME pool: rows of the block table are kept as they
+    are, group ids are renumbered densely (a group keeps its sharing)."""
+    seq_ids = np.asarray(seq_ids, dtype=np.int64)
+    assert len(seq_ids) and np.all(np.diff(seq_ids) > 0)
+    g_old = st.branch_group[seq_ids]
+    g_new = np.zeros(len(seq_ids), dtype=np.int32)
+    g_new[1:] = np.cumsum(g_old[1:] != g_old[:-1])
+    return BatchStructure(st.shape, np.ascontiguousarray(st.block_table[seq_ids]), g_new, st.prefix_len[seq_ids].copy(),
+                          st.suffix_len[seq_ids].copy(), st.n_pool_pages, name=st.name + "_subset", seed=st.seed)
+
+
 def compact_rows(st: BatchStructure, seq_ids: Sequence[int]) -> Tuple[BatchStructure, np.ndarray]:
     """Sub-batch holding only ``seq_ids`` (ascending), over a compact pool.
 
