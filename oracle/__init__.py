@@ -6,6 +6,10 @@ this package.  It never imports the GPU package.
 from .oracle import (  # noqa: F401
     OracleInts,
     attention,
+    attention_segments,
+    attention_slots,
+    kv_append,
+    resolve_segments,
     build,
     resolve,
 )

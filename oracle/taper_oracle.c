@@ -169,3 +169,106 @@ int taper_oracle_attention(int S, int Hq, int Hkv, int D, int P, double scale,
     }
     return used;
 }
+
+/* ------------------------------------------------------------------------
+ * Reduce phase and KV append (the two steps around the parallel phase).
+ *
+ * Reduce-phase visibility (paper §3.1): a reduce token attends to the shared
+ * prefix followed by ALL completed branches in canonical order and then the
+ * reduce tokens generated so far,
+ *     P ++ H ++ (h_1 ++ y_1) ++ ... ++ (h_n ++ y_n) ++ z_<t .
+ * In a paged cache every one of these pieces keeps the pages it was written
+ * to: the sequence's block-table row lists the prefix pages and then, piece by
+ * piece, the pages of each private segment; a segment starts on a fresh page,
+ * so partially filled pages occur in the middle of the context.  The context
+ * is therefore a list of physical slots, and attention over it is the same
+ * textbook sum as above.
+ * ------------------------------------------------------------------------ */
+
+/* Slot (page * P + token) of every logical position of sequences whose private
+ * context is a list of segments: seg_len[seg_start[s] .. seg_start[s+1]).
+ * ctx_len and n_private_pages are per sequence; slots is [S, stride], -1 past
+ * the end.  n_private_pages is also the memory the private part occupies
+ * (App. C memory accounting: blocks of branch-local tokens, none for an empty
+ * segment). */
+void taper_oracle_resolve_segments(int S, int P, const int32_t *block_table, int bt_stride,
+                                   const int32_t *prefix_len, const int32_t *seg_start,
+                                   const int32_t *seg_len, int32_t *ctx_len,
+                                   int32_t *n_private_pages, int64_t *slots, int64_t slots_stride)
+{
+    for (int s = 0; s < S; ++s) {
+        const int32_t *row = block_table + (int64_t)s * bt_stride;
+        int64_t t = 0;
+        int entry = 0, priv_pages = 0;
+        if (slots)
+            for (int64_t i = 0; i < slots_stride; ++i) slots[s * slots_stride + i] = -1;
+        for (int j = 0; j < prefix_len[s]; ++j, ++t)
+            if (slots && t < slots_stride) slots[s * slots_stride + t] = (int64_t)row[j / P] * P + j % P;
+        entry = (int)ceil_div(prefix_len[s], P);
+        for (int k = seg_start[s]; k < seg_start[s + 1]; ++k) {
+            for (int j = 0; j < seg_len[k]; ++j, ++t)
+                if (slots && t < slots_stride) slots[s * slots_stride + t] = (int64_t)row[entry + j / P] * P + j % P;
+            entry += (int)ceil_div(seg_len[k], P);
+            priv_pages += (int)ceil_div(seg_len[k], P);
+        }
+        ctx_len[s] = (int32_t)t;
+        n_private_pages[s] = priv_pages;
+    }
+}
+
+/* Attention of one query row per (sequence, head) over an explicit slot list. */
+int taper_oracle_attention_slots(int S, int Hq, int Hkv, int D, int P, double scale,
+                                 const uint16_t *q, const uint16_t *kv_pool, const int64_t *slots,
+                                 int64_t slots_stride, const int32_t *ctx_len, double *out, double *lse,
+                                 int n_threads)
+{
+    int g = Hq / Hkv;
+    int used = 1;
+#ifdef _OPENMP
+    if (n_threads > 0) omp_set_num_threads(n_threads);
+    used = omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int sh = 0; sh < S * Hq; ++sh) {
+        int s = sh / Hq, h = sh % Hq, hk = h / g;
+        const int64_t *sl = slots + (int64_t)s * slots_stride;
+        int n = ctx_len[s];
+        double *x = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+        double *o = out + ((int64_t)s * Hq + h) * D;
+        const uint16_t *qrow = q + ((int64_t)s * Hq + h) * D;
+        double m = -INFINITY;
+        for (int t = 0; t < n; ++t) {
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d)
+                acc += bf16_to_double(qrow[d]) * bf16_to_double(kv_pool[kv_elem(0, sl[t] / P, hk, (int)(sl[t] % P), d, Hkv, D, P)]);
+            x[t] = scale * acc;
+            if (x[t] > m) m = x[t];
+        }
+        double Z = 0.0;
+        for (int t = 0; t < n; ++t) { x[t] = exp(x[t] - m); Z += x[t]; }
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        for (int t = 0; t < n; ++t)
+            for (int d = 0; d < D; ++d)
+                o[d] += x[t] * bf16_to_double(kv_pool[kv_elem(1, sl[t] / P, hk, (int)(sl[t] % P), d, Hkv, D, P)]);
+        for (int d = 0; d < D; ++d) o[d] /= Z;
+        if (lse) lse[(int64_t)s * Hq + h] = m + log(Z);
+        free(x);
+    }
+    return used;
+}
+
+/* KV append: the step's new key and value rows (bf16 bits, [S][Hkv][D] each)
+ * are written to slot[s] of the pool -- the position right after the
+ * sequence's last cached token.  A pure copy into the tile layout above. */
+void taper_oracle_kv_append(int S, int Hkv, int D, int P, const uint16_t *k_new, const uint16_t *v_new,
+                            const int64_t *slot, uint16_t *kv_pool)
+{
+    for (int s = 0; s < S; ++s)
+        for (int hk = 0; hk < Hkv; ++hk)
+            for (int d = 0; d < D; ++d) {
+                int64_t page = slot[s] / P;
+                int tok = (int)(slot[s] % P);
+                kv_pool[kv_elem(0, page, hk, tok, d, Hkv, D, P)] = k_new[((int64_t)s * Hkv + hk) * D + d];
+                kv_pool[kv_elem(1, page, hk, tok, d, Hkv, D, P)] = v_new[((int64_t)s * Hkv + hk) * D + d];
+            }
+}

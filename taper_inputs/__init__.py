@@ -9,6 +9,8 @@ from .generators import (  # noqa: F401
     AttnShape,
     Batch,
     BatchStructure,
+    SegmentedStructure,
+    reduce_structure,
     CONFIG_SEED_BASE,
     bf16_bits_from_f32,
     f32_from_bf16_bits,

@@ -313,3 +313,89 @@ def compact_rows(st: BatchStructure, seq_ids: Sequence[int]) -> Tuple[BatchStruc
         g_new[1:] = np.cumsum(g_old[1:] != g_old[:-1])
     sub = BatchStructure(st.shape, bt_new, g_new, pl, sl, max(1, len(order)), name=st.name + "_sub", seed=st.seed)
     return sub, np.asarray(order, dtype=np.int64)
+
+
+# ---------------------------------------------------------------- segmented contexts (reduce phase)
+@dataclasses.dataclass
+class SegmentedStructure:
+    """A batch whose sequences see the shared prefix followed by a LIST of private segments, each written on
+    pages of its own (paper §3.1: a branch sees one private segment, h_i ++ y_i so far; a reduce token sees
+    every completed branch in canonical order and then the reduce tokens so far)."""
+
+    shape: AttnShape
+    block_table: np.ndarray  # int32 [S, max_blocks]: prefix pages, then each segment's pages in order
+    branch_group: np.ndarray  # int32 [S]
+    prefix_len: np.ndarray  # int32 [S], equal inside a group
+    seg_start: np.ndarray  # int32 [S + 1] CSR over seg_len
+    seg_len: np.ndarray  # int32, tokens of each private segment (may be 0: owns no page)
+    n_pool_pages: int
+    name: str = ""
+    seed: int = 0
+
+    @property
+    def n_seqs(self) -> int:
+        return int(self.block_table.shape[0])
+
+    @property
+    def private_len(self) -> np.ndarray:
+        return np.array([int(self.seg_len[self.seg_start[s]:self.seg_start[s + 1]].sum()) for s in range(self.n_seqs)],
+                        dtype=np.int64)
+
+    @property
+    def logical_tokens(self) -> int:
+        return int(self.prefix_len.astype(np.int64).sum() + self.private_len.sum())
+
+
+def reduce_structure(par: BatchStructure, z_len: Sequence[int], seed: int = 0, keep_parallel: Sequence[int] = ()) -> SegmentedStructure:
+    """The step after a parallel phase.  Every request (group) of ``par`` not listed in ``keep_parallel``
+    becomes ONE reduce sequence: its prefix pages, then the private pages of each of its branches in branch
+    order (the pages ``par`` gave them, partially filled last pages included), then ``z_len[g]`` reduce tokens
+    on fresh pages taken from the pool's unused pages.  Requests in ``keep_parallel`` stay as they are
+    (branches with one private segment each), so both phases can share a batch."""
+    P = par.shape.page_size
+    cdiv = lambda a: (int(a) + P - 1) // P
+    rng = np.random.Generator(np.random.PCG64(seed))
+    used = np.zeros(par.n_pool_pages, dtype=bool)
+    for s in range(par.n_seqs):
+        n = cdiv(par.prefix_len[s]) + cdiv(par.suffix_len[s])
+        used[par.block_table[s, :n]] = True
+    free = rng.permutation(np.flatnonzero(~used))
+    rows, grp, pl, segs = [], [], [], []
+    cur = 0
+    g_new = 0
+    first = np.flatnonzero(np.r_[True, par.branch_group[1:] != par.branch_group[:-1]])
+    bounds = np.r_[first, par.n_seqs]
+    for g in range(par.n_groups):
+        a, b = int(bounds[g]), int(bounds[g + 1])
+        npp = cdiv(par.prefix_len[a])
+        if g in keep_parallel:
+            for s in range(a, b):
+                rows.append(list(par.block_table[s, : npp + cdiv(par.suffix_len[s])]))
+                grp.append(g_new)
+                pl.append(int(par.prefix_len[s]))
+                segs.append([int(par.suffix_len[s])])
+        else:
+            row = list(par.block_table[a, :npp])
+            seg = []
+            for s in range(a, b):
+                row += list(par.block_table[s, npp : npp + cdiv(par.suffix_len[s])])
+                seg.append(int(par.suffix_len[s]))
+            nz = cdiv(z_len[g])
+            assert cur + nz <= len(free), "pool has too few unused pages for the reduce tokens"
+            row += list(free[cur : cur + nz])
+            cur += nz
+            seg.append(int(z_len[g]))
+            rows.append(row)
+            grp.append(g_new)
+            pl.append(int(par.prefix_len[a]))
+            segs.append(seg)
+        g_new += 1
+    width = max(len(r) for r in rows)
+    bt = np.full((len(rows), max(width, 1)), -1, dtype=np.int32)
+    for i, r in enumerate(rows):
+        bt[i, : len(r)] = r
+    seg_start = np.zeros(len(rows) + 1, dtype=np.int32)
+    seg_start[1:] = np.cumsum([len(x) for x in segs])
+    seg_len = np.array([v for x in segs for v in x], dtype=np.int32)
+    return SegmentedStructure(par.shape, bt, np.array(grp, np.int32), np.array(pl, np.int32), seg_start, seg_len,
+                              par.n_pool_pages, name=par.name + "_reduce", seed=seed)
