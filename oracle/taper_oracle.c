@@ -233,7 +233,7 @@ int taper_oracle_attention_slots(int S, int Hq, int Hkv, int D, int P, double sc
         int s = sh / Hq, h = sh % Hq, hk = h / g;
         const int64_t *sl = slots + (int64_t)s * slots_stride;
         int n = ctx_len[s];
-        double *x = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+        double *w = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
         double *o = out + ((int64_t)s * Hq + h) * D;
         const uint16_t *qrow = q + ((int64_t)s * Hq + h) * D;
         double m = -INFINITY;
@@ -241,18 +241,21 @@ int taper_oracle_attention_slots(int S, int Hq, int Hkv, int D, int P, double sc
             double acc = 0.0;
             for (int d = 0; d < D; ++d)
                 acc += bf16_to_double(qrow[d]) * bf16_to_double(kv_pool[kv_elem(0, sl[t] / P, hk, (int)(sl[t] % P), d, Hkv, D, P)]);
-            x[t] = scale * acc;
-            if (x[t] > m) m = x[t];
+            w[t] = acc * scale;
+            if (w[t] > m) m = w[t];
         }
         double Z = 0.0;
-        for (int t = 0; t < n; ++t) { x[t] = exp(x[t] - m); Z += x[t]; }
+        for (int t = 0; t < n; ++t) {
+            w[t] = exp(w[t] - m);
+            Z += w[t];
+        }
         for (int d = 0; d < D; ++d) o[d] = 0.0;
         for (int t = 0; t < n; ++t)
             for (int d = 0; d < D; ++d)
-                o[d] += x[t] * bf16_to_double(kv_pool[kv_elem(1, sl[t] / P, hk, (int)(sl[t] % P), d, Hkv, D, P)]);
+                o[d] += w[t] * bf16_to_double(kv_pool[kv_elem(1, sl[t] / P, hk, (int)(sl[t] % P), d, Hkv, D, P)]);
         for (int d = 0; d < D; ++d) o[d] /= Z;
         if (lse) lse[(int64_t)s * Hq + h] = m + log(Z);
-        free(x);
+        free(w);
     }
     return used;
 }
