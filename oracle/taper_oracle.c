@@ -230,7 +230,8 @@ int taper_oracle_attention_slots(int S, int Hq, int Hkv, int D, int P, double sc
 #pragma omp parallel for schedule(dynamic, 1)
 #endif
     for (int sh = 0; sh < S * Hq; ++sh) {
-        int s = sh / Hq, h = sh % Hq, hk = h / g;
+        int s = sh / Hq, h = sh % Hq;
+        int hk = (h - h % g) / g; /* grouped-query map: g consecutive query heads per KV head */
         const int64_t *sl = slots + (int64_t)s * slots_stride;
         int n = ctx_len[s];
         double *w = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
