@@ -113,6 +113,9 @@ typedef struct {
     const int32_t *n_suffix_pages; /* [n_seqs] ceil(suffix_len / page_size): the branch's
                                       marginal blocks (App. C), 0 for an empty branch       */
     const int32_t *group_start;    /* [n_groups + 1] CSR of requests over sequences         */
+    const int32_t *seg_start;      /* [n_seqs + 1] CSR of private segments over sequences   */
+    const int32_t *seg_len;        /* tokens of each private segment                        */
+    const int32_t *seg_page0;      /* block-table entry each private segment starts at      */
     int32_t n_items;
     const taper_work_item *items;  /* [n_items], ordered by part, then the n_pool_items pool items */
     int32_t n_pool_items;
@@ -166,6 +169,25 @@ TAPER_API int taper_plan_build(taper_ctx *ctx, int n_seqs, const int32_t *block_
                      const int32_t *suffix_len /* host */, int64_t n_pool_pages,
                      const taper_plan_options *opts /* host, may be NULL */, void *hip_stream,
                      taper_plan **out_plan);
+/*
+ * The same with a LIST of private segments per sequence (reduce-phase visibility,
+ * paper §3.1: a reduce token attends to the shared prefix, then to every
+ * completed branch in canonical order, then to the reduce tokens so far).
+ * Sequence s sees prefix_len[s] prefix tokens and then the segments
+ * seg_len[seg_start[s] .. seg_start[s+1]) in that order.  Its block-table row
+ * lists the prefix pages and then each segment's pages; every segment starts on
+ * a fresh page (so the pages a branch wrote during the parallel phase are
+ * listed as they are, partially filled last page included) and an empty
+ * segment owns no page.  taper_plan_build is the case of one segment per
+ * sequence.  In the plan's view suffix_len-derived fields are totals over a
+ * sequence's segments.  TAPER_EINVAL for a malformed CSR.
+ */
+TAPER_API int taper_plan_build_segments(taper_ctx *ctx, int n_seqs, const int32_t *block_table /* host */,
+                                        int bt_row_stride, const int32_t *branch_group /* host */,
+                                        const int32_t *prefix_len /* host */, const int32_t *seg_start /* host */,
+                                        const int32_t *seg_len /* host */, int64_t n_pool_pages,
+                                        const taper_plan_options *opts /* host, may be NULL */, void *hip_stream,
+                                        taper_plan **out_plan);
 TAPER_API void taper_plan_free(taper_plan *plan);
 TAPER_API int taper_plan_export(const taper_plan *plan, taper_plan_view *out_view /* host */);
 
@@ -233,6 +255,39 @@ TAPER_API int taper_step_latency_probe(taper_ctx *ctx, const taper_plan *plan, i
  */
 TAPER_API int taper_kernel_times(taper_ctx *ctx, const taper_plan *plan, const void *q, const void *kv_pages, void *out,
                        int warmup, int iters, void *hip_stream, double us[2] /* host */);
+
+/*
+ * KV append: the step before attention in a decode loop.  The token a sequence
+ * generated in the previous step becomes part of its context: its key and value
+ * rows are written into the sequence's last private segment, right after that
+ * segment's last token.  When the segment's pages are full (its length is a
+ * multiple of page_size, 0 included) the token opens a new page, which the
+ * caller must already have entered in the block table -- this is the only
+ * moment a branch's memory grows (paper App. C "Memory accounting":
+ * dM(j) = blocks(branch-local tokens), 0 for a branch that has produced nothing).
+ *
+ * taper_append_slots (host, integers only): slot[s] = page * page_size + token
+ * where sequence s's next token goes, and opens_page[s] (may be NULL) = 1 when
+ * that token is the first of a page.  Same batch arrays as
+ * taper_plan_build_segments, lengths BEFORE the append.  TAPER_ELEN when a row
+ * has no entry for the page, TAPER_EBLOCK when the entry is outside the pool,
+ * TAPER_EINVAL when a sequence has no private segment.
+ *
+ * taper_kv_append: k_new, v_new bf16 [n_seqs][n_kv_heads][head_dim] (device),
+ * slots int64 [n_seqs] (device), kv_pages the pool (device, written).  Enqueues
+ * one kernel on hip_stream; allocates nothing, does not synchronise.  Slots must
+ * be distinct.
+ *
+ * taper_branch_blocks: blocks(L) = ceil(L / page_size), the pages a branch with L
+ * branch-local tokens occupies.
+ */
+TAPER_API int taper_append_slots(int n_seqs, const int32_t *block_table /* host */, int bt_row_stride,
+                                 const int32_t *prefix_len /* host */, const int32_t *seg_start /* host */,
+                                 const int32_t *seg_len /* host */, int page_size, int64_t n_pool_pages,
+                                 int64_t *slots /* host, out */, int32_t *opens_page /* host, out, may be NULL */);
+TAPER_API int taper_kv_append(taper_ctx *ctx, int n_seqs, const void *k_new /* device */, const void *v_new /* device */,
+                              const int64_t *slots /* device */, void *kv_pages /* device */, void *hip_stream);
+TAPER_API int64_t taper_branch_blocks(int64_t branch_local_tokens, int page_size);
 
 TAPER_API const char *taper_strerror(int status);
 TAPER_API const char *taper_last_error(void);

@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     Plan,
     Window,
     admit_step,
+    append_slots,
+    branch_blocks,
     predictor_eval,
     predictor_fit,
     predictor_mape,

@@ -23,6 +23,7 @@ EXPORTED = [
     "taper_plan_resolve_slots_host", "taper_plan_resolve_slots", "taper_decode_step_attention",
     "taper_decode_step_attention_simple", "taper_step_latency_probe", "taper_kernel_times",
     "taper_strerror", "taper_last_error",
+    "taper_plan_build_segments", "taper_append_slots", "taper_kv_append", "taper_branch_blocks",
     "taper_predictor_fit", "taper_predictor_eval", "taper_predictor_mape", "taper_window_create",
     "taper_window_destroy", "taper_window_push", "taper_window_size", "taper_window_fit", "taper_admit_step",
 ]
@@ -48,6 +49,7 @@ _I32P = ctypes.POINTER(ctypes.c_int32)
 class taper_plan_view(ctypes.Structure):
     _fields_ = [("n_seqs", ctypes.c_int32), ("n_groups", ctypes.c_int32), ("ctx_len", _I32P),
                 ("n_prefix_pages", _I32P), ("n_suffix_pages", _I32P), ("group_start", _I32P),
+                ("seg_start", _I32P), ("seg_len", _I32P), ("seg_page0", _I32P),
                 ("n_items", ctypes.c_int32), ("items", ctypes.POINTER(taper_work_item)),
                 ("n_pool_items", ctypes.c_int32),
                 ("n_parts_shared", ctypes.c_int32), ("n_parts_private", ctypes.c_int32), ("part_start", _I32P),
@@ -115,6 +117,12 @@ def load_library() -> ctypes.CDLL:
     lib.taper_destroy.restype = None
     lib.taper_plan_build.argtypes = [vp, ci, vp, ci, vp, vp, vp, i64, ctypes.POINTER(taper_plan_options), vp,
                                      ctypes.POINTER(vp)]
+    lib.taper_plan_build_segments.argtypes = [vp, ci, vp, ci, vp, vp, vp, vp, i64, ctypes.POINTER(taper_plan_options), vp,
+                                              ctypes.POINTER(vp)]
+    lib.taper_append_slots.argtypes = [ci, vp, ci, vp, vp, vp, ci, i64, vp, vp]
+    lib.taper_kv_append.argtypes = [vp, ci, vp, vp, vp, vp, vp]
+    lib.taper_branch_blocks.argtypes = [i64, ci]
+    lib.taper_branch_blocks.restype = i64
     lib.taper_plan_free.argtypes = [vp]
     lib.taper_plan_free.restype = None
     lib.taper_plan_export.argtypes = [vp, ctypes.POINTER(taper_plan_view)]
@@ -199,9 +207,12 @@ class Plan:
         arr = lambda p, n: np.ctypeslib.as_array(p, shape=(n,)).copy() if n else np.zeros(0, np.int32)
         items = np.ctypeslib.as_array(ctypes.cast(v.items, _I32P), shape=(v.n_items, 8)).copy()
         n_merge = int(arr(v.merge_start, S + 1)[-1])
+        seg_start = arr(v.seg_start, S + 1)
+        n_seg = int(seg_start[-1])
         merge = np.ctypeslib.as_array(ctypes.cast(v.merge, _I32P), shape=(n_merge, 2)).copy()
         return dict(n_seqs=S, n_groups=G, ctx_len=arr(v.ctx_len, S), n_prefix_pages=arr(v.n_prefix_pages, S),
                     n_suffix_pages=arr(v.n_suffix_pages, S), group_start=arr(v.group_start, G + 1),
+                    seg_start=seg_start, seg_len=arr(v.seg_len, n_seg), seg_page0=arr(v.seg_page0, n_seg),
                     items=items, item_fields=[f[0] for f in taper_work_item._fields_],
                     n_pool_items=v.n_pool_items, n_parts_shared=v.n_parts_shared, n_parts_private=v.n_parts_private,
                     part_start=arr(v.part_start, n_parts + 1), merge_start=arr(v.merge_start, S + 1), merge=merge,
@@ -258,6 +269,33 @@ class Context:
                                                pl.ctypes.data, sl.ctypes.data, int(n_pool_pages), ctypes.byref(opts),
                                                st, ctypes.byref(h)))
         return Plan(self, h.value)
+
+    def plan_build_segments(self, block_table, branch_group, prefix_len, seg_start, seg_len, n_pool_pages: int,
+                            stream=None, **options) -> Plan:
+        """Plan for sequences that see their prefix and then a list of private segments (reduce phase)."""
+        bt = _i32(block_table)
+        grp, pl, ss, sl = _i32(branch_group), _i32(prefix_len), _i32(seg_start), _i32(seg_len)
+        if bt.ndim != 2 or not (len(grp) == len(pl) == bt.shape[0] == len(ss) - 1) or (len(ss) and ss[-1] != len(sl)):
+            raise TaperError(TAPER_EINVAL, "block_table must be [S, max_blocks], seg_start length S + 1 ending at len(seg_len)")
+        names = ["target_workgroups", "share_prefix", "max_branches_per_item", "shared_cost_pct", "shared_item_cost",
+                 "private_item_cost", "pool_pct", "pool_item_tokens"]
+        vals = {n: 0 for n in names}
+        vals["share_prefix"] = 1
+        for k, v in options.items():
+            if k not in vals:
+                raise TypeError(f"unknown plan option {k}")
+            vals[k] = int(v)
+        opts = taper_plan_options(*[vals[n] for n in names])
+        h = ctypes.c_void_p()
+        st = 0 if self.cfg.device < 0 else _stream(stream)
+        _check(load_library().taper_plan_build_segments(self._h, bt.shape[0], bt.ctypes.data, bt.shape[1], grp.ctypes.data,
+                                                        pl.ctypes.data, ss.ctypes.data, sl.ctypes.data if len(sl) else None,
+                                                        int(n_pool_pages), ctypes.byref(opts), st, ctypes.byref(h)))
+        return Plan(self, h.value)
+
+    def kv_append(self, k_new, v_new, slots_dev, kv_pages, n_seqs: int, stream=None):
+        _check(load_library().taper_kv_append(self._h, int(n_seqs), _ptr(k_new), _ptr(v_new), _ptr(slots_dev),
+                                              _ptr(kv_pages), _stream(stream)))
 
     def decode_step_attention(self, plan: Plan, q, kv_pages, out, lse=None, stream=None):
         _check(load_library().taper_decode_step_attention(self._h, plan._h, _ptr(q), _ptr(kv_pages), _ptr(out),
@@ -374,3 +412,22 @@ def admit_step(coef, base_context, slack_ms, branch_context, rho=1.0, utility="l
                                 w.ctypes.data if w is not None else None, tab.ctypes.data if tab is not None else None,
                                 ctypes.byref(opts), granted.ctypes.data, ctypes.byref(res)))
     return granted, {f[0]: getattr(res, f[0]) for f in taper_admission_result._fields_}
+
+
+def append_slots(block_table, prefix_len, seg_start, seg_len, page_size: int, n_pool_pages: int):
+    """Where each sequence's next token goes: (slots int64 [S], opens_page int32 [S])."""
+    bt = _i32(block_table)
+    pl, ss, sl = _i32(prefix_len), _i32(seg_start), _i32(seg_len)
+    S = bt.shape[0]
+    if len(pl) != S or len(ss) != S + 1 or ss[-1] != len(sl):
+        raise TaperError(TAPER_EINVAL, "per-sequence arrays do not match the block table")
+    slots = np.zeros(S, np.int64)
+    opens = np.zeros(S, np.int32)
+    _check(load_library().taper_append_slots(S, bt.ctypes.data, bt.shape[1], pl.ctypes.data, ss.ctypes.data,
+                                             sl.ctypes.data if len(sl) else None, page_size, int(n_pool_pages),
+                                             slots.ctypes.data, opens.ctypes.data))
+    return slots, opens
+
+
+def branch_blocks(branch_local_tokens: int, page_size: int = 16) -> int:
+    return int(load_library().taper_branch_blocks(int(branch_local_tokens), page_size))

@@ -67,7 +67,9 @@ struct taper_plan {
     const int32_t* d_merge_start = nullptr;
     const taper_merge_entry* d_merge = nullptr;
     const int32_t* d_prefix_len = nullptr;
-    const int32_t* d_n_prefix_pages = nullptr;
+    const int32_t* d_seg_start = nullptr;
+    const int32_t* d_seg_len = nullptr;
+    const int32_t* d_seg_page0 = nullptr;
     const int32_t* d_ctx_len = nullptr;
 };
 
@@ -156,7 +158,9 @@ taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const vo
     a.merge_start = plan->d_merge_start;
     a.merge = plan->d_merge;
     a.prefix_len = plan->d_prefix_len;
-    a.n_prefix_pages = plan->d_n_prefix_pages;
+    a.seg_start = plan->d_seg_start;
+    a.seg_len = plan->d_seg_len;
+    a.seg_page0 = plan->d_seg_page0;
     a.ctx_len = plan->d_ctx_len;
     a.counters = (int32_t*)ctx->ws;
     a.pool_ctr = a.counters + (int64_t)plan->host.n_seqs * ctx->cfg.n_kv_heads;
@@ -211,6 +215,49 @@ const char* taper_strerror(int status) {
 
 const char* taper_last_error(void) { return g_last_error.c_str(); }
 
+int taper_append_slots(int n_seqs, const int32_t* block_table, int bt_row_stride, const int32_t* prefix_len,
+                       const int32_t* seg_start, const int32_t* seg_len, int page_size, int64_t n_pool_pages,
+                       int64_t* slots, int32_t* opens_page) {
+    if (!block_table || !prefix_len || !seg_start || !seg_len || !slots) return fail(TAPER_EINVAL, "null argument");
+    if (n_seqs < 0 || bt_row_stride < 1 || page_size < 1 || n_pool_pages < 1) return fail(TAPER_EINVAL, "bad argument");
+    const int64_t P = page_size;
+    for (int s = 0; s < n_seqs; ++s) {
+        if (seg_start[s + 1] <= seg_start[s])
+            return fail(TAPER_EINVAL, "sequence " + std::to_string(s) + " has no private segment to append to");
+        if (prefix_len[s] < 0) return fail(TAPER_ELEN, "negative length");
+        int64_t entry = (prefix_len[s] + P - 1) / P;
+        for (int k = seg_start[s]; k < seg_start[s + 1] - 1; ++k) {
+            if (seg_len[k] < 0) return fail(TAPER_ELEN, "negative length");
+            entry += (seg_len[k] + P - 1) / P;
+        }
+        const int64_t last = seg_len[seg_start[s + 1] - 1];
+        if (last < 0) return fail(TAPER_ELEN, "negative length");
+        entry += last / P;
+        if (entry >= bt_row_stride)
+            return fail(TAPER_ELEN, "sequence " + std::to_string(s) + ": block-table row has no entry for the new token's page");
+        const int64_t page = block_table[(size_t)s * bt_row_stride + entry];
+        if (page < 0 || page >= n_pool_pages)
+            return fail(TAPER_EBLOCK, "sequence " + std::to_string(s) + ": page of the new token is outside the pool");
+        slots[s] = page * P + last % P;
+        if (opens_page) opens_page[s] = last % P == 0;
+    }
+    return TAPER_OK;
+}
+
+int taper_kv_append(taper_ctx* ctx, int n_seqs, const void* k_new, const void* v_new, const int64_t* slots, void* kv_pages,
+                    void* hip_stream) {
+    if (!ctx || !k_new || !v_new || !slots || !kv_pages || n_seqs < 0) return fail(TAPER_EINVAL, "bad argument");
+    if (ctx->host_only) return fail(TAPER_EHIP, "host-only context: no device work possible");
+    HIP_TRY(taper::launch_kv_append(k_new, v_new, slots, kv_pages, n_seqs, ctx->cfg.n_kv_heads, ctx->cfg.head_dim,
+                                    (hipStream_t)hip_stream));
+    return TAPER_OK;
+}
+
+int64_t taper_branch_blocks(int64_t branch_local_tokens, int page_size) {
+    if (branch_local_tokens <= 0 || page_size < 1) return 0;
+    return (branch_local_tokens + page_size - 1) / page_size;
+}
+
 int taper_create(const taper_attn_config* cfg, taper_ctx** out_ctx) {
     if (!cfg || !out_ctx) return fail(TAPER_EINVAL, "null argument");
     std::string err;
@@ -248,13 +295,24 @@ void taper_destroy(taper_ctx* ctx) {
 int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int bt_row_stride,
                      const int32_t* branch_group, const int32_t* prefix_len, const int32_t* suffix_len,
                      int64_t n_pool_pages, const taper_plan_options* opts, void* hip_stream, taper_plan** out_plan) {
+    if (!suffix_len || n_seqs < 1) return fail(TAPER_EINVAL, "null argument");
+    std::vector<int32_t> seg_start((size_t)n_seqs + 1);
+    for (int s = 0; s <= n_seqs; ++s) seg_start[s] = s;  // one private segment per sequence
+    return taper_plan_build_segments(ctx, n_seqs, block_table, bt_row_stride, branch_group, prefix_len, seg_start.data(),
+                                     suffix_len, n_pool_pages, opts, hip_stream, out_plan);
+}
+
+int taper_plan_build_segments(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int bt_row_stride,
+                              const int32_t* branch_group, const int32_t* prefix_len, const int32_t* seg_start,
+                              const int32_t* seg_len, int64_t n_pool_pages, const taper_plan_options* opts,
+                              void* hip_stream, taper_plan** out_plan) {
     if (!ctx || !out_plan) return fail(TAPER_EINVAL, "null argument");
     taper_plan* plan = new (std::nothrow) taper_plan();
     if (!plan) return fail(TAPER_ENOMEM, "host allocation failed");
     plan->ctx = ctx;
     std::string err;
-    int st = taper::build_host_plan(ctx->cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len,
-                                    suffix_len, n_pool_pages, opts, &plan->host, &err);
+    int st = taper::build_host_plan_segments(ctx->cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len,
+                                             seg_start, seg_len, n_pool_pages, opts, &plan->host, &err);
     if (st != TAPER_OK) {
         delete plan;
         return fail(st, err);
@@ -264,7 +322,7 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
         return TAPER_OK;
     }
     const taper::HostPlan& h = plan->host;
-    // one image: bt | items | part_start | merge_start | merge | prefix_len | n_prefix_pages | ctx_len
+    // one image: bt | items | part_start | merge_start | merge | prefix_len | seg_start | ctx_len | seg_len | seg_page0
     struct Piece {
         const void* src;
         size_t bytes;
@@ -277,8 +335,10 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
         {h.merge_start.data(), h.merge_start.size() * sizeof(int32_t), 0},
         {h.merge.data(), h.merge.size() * sizeof(taper_merge_entry), 0},
         {h.prefix_len.data(), h.prefix_len.size() * sizeof(int32_t), 0},
-        {h.n_prefix_pages.data(), h.n_prefix_pages.size() * sizeof(int32_t), 0},
+        {h.seg_start.data(), h.seg_start.size() * sizeof(int32_t), 0},
         {h.ctx_len.data(), h.ctx_len.size() * sizeof(int32_t), 0},
+        {h.seg_len.data(), h.seg_len.size() * sizeof(int32_t), 0},
+        {h.seg_page0.data(), h.seg_page0.size() * sizeof(int32_t), 0},
     };
     size_t total = 0;
     for (Piece& p : pieces) {
@@ -311,8 +371,10 @@ int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int
     plan->d_merge_start = (const int32_t*)(d + pieces[3].off);
     plan->d_merge = (const taper_merge_entry*)(d + pieces[4].off);
     plan->d_prefix_len = (const int32_t*)(d + pieces[5].off);
-    plan->d_n_prefix_pages = (const int32_t*)(d + pieces[6].off);
+    plan->d_seg_start = (const int32_t*)(d + pieces[6].off);
     plan->d_ctx_len = (const int32_t*)(d + pieces[7].off);
+    plan->d_seg_len = (const int32_t*)(d + pieces[8].off);
+    plan->d_seg_page0 = (const int32_t*)(d + pieces[9].off);
     st = ensure_workspace(ctx, h.n_partial_rows, ((int64_t)h.n_seqs + 1) * ctx->cfg.n_kv_heads);
     if (st != TAPER_OK) {
         std::string keep = g_last_error;
@@ -342,6 +404,9 @@ int taper_plan_export(const taper_plan* plan, taper_plan_view* v) {
     v->n_prefix_pages = h.n_prefix_pages.data();
     v->n_suffix_pages = h.n_suffix_pages.data();
     v->group_start = h.group_start.data();
+    v->seg_start = h.seg_start.data();
+    v->seg_len = h.seg_len.data();
+    v->seg_page0 = h.seg_page0.data();
     v->n_items = (int32_t)h.items.size();
     v->items = h.items.data();
     v->n_pool_items = h.n_pool_items;

@@ -20,7 +20,9 @@ struct StepArgs {
     const int32_t* merge_start;
     const taper_merge_entry* merge;
     const int32_t* prefix_len;
-    const int32_t* n_prefix_pages;
+    const int32_t* seg_start;      // [n_seqs + 1] private segments of each sequence
+    const int32_t* seg_len;        // tokens of each private segment
+    const int32_t* seg_page0;      // block-table entry each private segment starts at
     const int32_t* ctx_len;
     float2* ws_ml;             // [n_partial_rows] (running max in log2 units, sum)
     float* ws_o;               // [n_partial_rows][D] unnormalised
@@ -37,6 +39,8 @@ struct StepArgs {
 };
 
 hipError_t launch_decode(const StepArgs& a, hipStream_t s);
+hipError_t launch_kv_append(const void* k_new, const void* v_new, const int64_t* slot, void* kv, int n_seqs, int n_kv_heads,
+                            int head_dim, hipStream_t s);
 hipError_t launch_resolve_slots(const StepArgs& a, int64_t* slots, int64_t stride, hipStream_t s);
 
 }  // namespace taper

@@ -662,14 +662,50 @@ __global__ __launch_bounds__(256) void resolve_slots_kernel(StepArgs a, int64_t*
         if (t < pl) {
             v = (int64_t)row[t >> 4] * 16 + (t & 15);
         } else {
-            const int64_t jj = t - pl;
-            v = (int64_t)row[a.n_prefix_pages[s] + (jj >> 4)] * 16 + (jj & 15);
+            int64_t jj = t - pl;
+            int k = a.seg_start[s];
+            while (jj >= a.seg_len[k]) jj -= a.seg_len[k++];  // t < ctx_len: k stays inside the sequence's segments
+            v = (int64_t)row[a.seg_page0[k] + (jj >> 4)] * 16 + (jj & 15);
         }
     }
     slots[(int64_t)s * stride + t] = v;
 }
 
+// KV append: the new key and value rows of every sequence (bf16 [S][Hkv][D]) go to
+// slot[s] = page * 16 + token of the pool, in the tile layouts the attention kernels read:
+// K element d at (d/8)*128 + tok*8 + d%8 (16-byte groups of 8 dims), V element d at
+// (tok/4)*4D + d*4 + tok%4.  One workgroup per sequence, thread = (kv head, group of 8 dims).
+__global__ __launch_bounds__(256) void kv_append_kernel(const __bf16* __restrict__ k_new, const __bf16* __restrict__ v_new,
+                                                        const int64_t* __restrict__ slot, __bf16* __restrict__ kv,
+                                                        const int n_kv_heads, const int D) {
+    const int s = blockIdx.x;
+    const int64_t sl = slot[s];
+    const int64_t page = sl >> 4;
+    const int tok = (int)(sl & 15);
+    const int groups = D / 8;
+    const int64_t tile = 16LL * D;
+    for (int i = threadIdx.x; i < n_kv_heads * groups; i += blockDim.x) {
+        const int hk = i / groups, d8 = i % groups;
+        const int64_t src = ((int64_t)s * n_kv_heads + hk) * D + 8 * d8;
+        const bf16x8 kx = *(const bf16x8*)(k_new + src);
+        const bf16x8 vx = *(const bf16x8*)(v_new + src);
+        __bf16* kt = kv + ((page * 2 + 0) * n_kv_heads + hk) * tile;
+        __bf16* vt = kv + ((page * 2 + 1) * n_kv_heads + hk) * tile;
+        *(bf16x8*)(kt + d8 * 128 + tok * 8) = kx;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vt[(tok >> 2) * (4 * D) + (8 * d8 + j) * 4 + (tok & 3)] = vx[j];
+    }
+}
+
 // ---------------------------------------------------------------------------
+hipError_t launch_kv_append(const void* k_new, const void* v_new, const int64_t* slot, void* kv, int n_seqs, int n_kv_heads,
+                            int head_dim, hipStream_t s) {
+    if (n_seqs == 0) return hipSuccess;
+    hipLaunchKernelGGL(kv_append_kernel, dim3(n_seqs), dim3(256), 0, s, (const __bf16*)k_new, (const __bf16*)v_new, slot,
+                       (__bf16*)kv, n_kv_heads, head_dim);
+    return hipGetLastError();
+}
+
 hipError_t launch_decode(const StepArgs& a, hipStream_t s) {
     const int n_parts = a.n_parts_shared + a.n_parts_private;
     if (n_parts == 0) return hipSuccess;

@@ -173,9 +173,23 @@ int partition_even(const std::vector<Segment>& segs, int64_t quota, int blk, con
 int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* block_table, int bt_row_stride,
                     const int32_t* branch_group, const int32_t* prefix_len, const int32_t* suffix_len,
                     int64_t n_pool_pages, const taper_plan_options* opts, HostPlan* out, std::string* err) {
+    if (!suffix_len || n_seqs < 1) {
+        *err = "null argument";
+        return TAPER_EINVAL;
+    }
+    std::vector<int32_t> seg_start(n_seqs + 1);
+    for (int s = 0; s <= n_seqs; ++s) seg_start[s] = s;  // one private segment per sequence
+    return build_host_plan_segments(cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len, seg_start.data(),
+                                    suffix_len, n_pool_pages, opts, out, err);
+}
+
+int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int32_t* block_table, int bt_row_stride,
+                             const int32_t* branch_group, const int32_t* prefix_len, const int32_t* seg_start,
+                             const int32_t* seg_len, int64_t n_pool_pages, const taper_plan_options* opts,
+                             HostPlan* out, std::string* err) {
     int st = validate_config(cfg, err);
     if (st != TAPER_OK) return st;
-    if (!block_table || !branch_group || !prefix_len || !suffix_len || !out) {
+    if (!block_table || !branch_group || !prefix_len || !seg_start || !out) {
         *err = "null argument";
         return TAPER_EINVAL;
     }
@@ -203,7 +217,24 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
     p.bt_stride = bt_row_stride;
     p.n_pool_pages = n_pool_pages;
     p.prefix_len.assign(prefix_len, prefix_len + n_seqs);
-    p.suffix_len.assign(suffix_len, suffix_len + n_seqs);
+    // private segments: CSR per sequence, lengths, and the block-table entry each one starts at
+    if (seg_start[0] != 0) {
+        *err = "seg_start[0] must be 0";
+        return TAPER_EINVAL;
+    }
+    for (int s = 0; s < n_seqs; ++s)
+        if (seg_start[s + 1] < seg_start[s]) {
+            *err = fmt("sequence %lld: seg_start must not decrease", s);
+            return TAPER_EINVAL;
+        }
+    if (seg_start[n_seqs] > 0 && !seg_len) {
+        *err = "null argument";
+        return TAPER_EINVAL;
+    }
+    p.seg_start.assign(seg_start, seg_start + n_seqs + 1);
+    p.seg_len.assign(seg_len, seg_len + seg_start[n_seqs]);
+    p.seg_page0.assign(seg_start[n_seqs], 0);
+    p.suffix_len.assign(n_seqs, 0);
     p.ctx_len.resize(n_seqs);
     p.n_prefix_pages.resize(n_seqs);
     p.n_suffix_pages.resize(n_seqs);
@@ -211,10 +242,21 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
 
     // ---- validation + per-sequence integers
     for (int s = 0; s < n_seqs; ++s) {
-        const int64_t pl = prefix_len[s], sl = suffix_len[s];
-        if (pl < 0 || sl < 0) {
+        const int64_t pl = prefix_len[s];
+        int64_t sl = 0, nsp = 0;
+        if (pl < 0) {
             *err = fmt("sequence %lld: negative length", s);
             return TAPER_ELEN;
+        }
+        const int64_t npp = (pl + P - 1) / P;
+        for (int k = seg_start[s]; k < seg_start[s + 1]; ++k) {
+            if (seg_len[k] < 0) {
+                *err = fmt("sequence %lld: negative length", s);
+                return TAPER_ELEN;
+            }
+            p.seg_page0[k] = (int32_t)std::min<int64_t>(npp + nsp, INT32_MAX);
+            sl += seg_len[k];
+            nsp += (seg_len[k] + P - 1) / P;
         }
         if (pl + sl < 1) {
             *err = fmt("sequence %lld: empty context", s);
@@ -224,7 +266,7 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
             *err = fmt("sequence %lld: context too long", s);
             return TAPER_ELEN;
         }
-        const int64_t npp = (pl + P - 1) / P, nsp = (sl + P - 1) / P;
+        p.suffix_len[s] = (int32_t)sl;
         if (npp + nsp > bt_row_stride) {
             *err = fmt("sequence %lld: needs %lld block-table entries, row has %lld", s, npp + nsp, bt_row_stride);
             return TAPER_ELEN;
@@ -295,8 +337,9 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
             }
         }
         for (int s = a; s < b; ++s) {
-            p.tokens_unique += suffix_len[s];
-            if (suffix_len[s] > 0) priv.push_back({s, 1, p.n_prefix_pages[s], suffix_len[s], 1});
+            p.tokens_unique += p.suffix_len[s];
+            for (int k = seg_start[s]; k < seg_start[s + 1]; ++k)
+                if (seg_len[k] > 0) priv.push_back({s, 1, p.seg_page0[k], seg_len[k], 1});
         }
     }
 
@@ -414,8 +457,10 @@ void resolve_slots_host(const HostPlan& p, int P, int64_t* slots, int64_t stride
                 if (t < p.prefix_len[s]) {
                     v = (int64_t)row[t / P] * P + t % P;
                 } else {
-                    const int64_t j = t - p.prefix_len[s];
-                    v = (int64_t)row[p.n_prefix_pages[s] + j / P] * P + j % P;
+                    int64_t j = t - p.prefix_len[s];
+                    int k = p.seg_start[s];
+                    while (j >= p.seg_len[k]) j -= p.seg_len[k++];
+                    v = (int64_t)row[p.seg_page0[k] + j / P] * P + j % P;
                 }
             }
             slots[(size_t)s * stride + t] = v;

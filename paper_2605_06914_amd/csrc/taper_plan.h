@@ -18,6 +18,7 @@ struct HostPlan {
     int64_t n_pool_pages = 0;
     std::vector<int32_t> block_table;  // [n_seqs * bt_stride], entries past a row's pages set to -1
     std::vector<int32_t> prefix_len, suffix_len, ctx_len, n_prefix_pages, n_suffix_pages;
+    std::vector<int32_t> seg_start, seg_len, seg_page0;  // private segments: CSR [n_seqs + 1], tokens, first block-table entry
     std::vector<int32_t> group_start;  // [n_groups + 1]
     std::vector<taper_work_item> items;
     int n_parts_shared = 0, n_parts_private = 0;
@@ -34,6 +35,13 @@ struct HostPlan {
 int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* block_table, int bt_row_stride,
                     const int32_t* branch_group, const int32_t* prefix_len, const int32_t* suffix_len,
                     int64_t n_pool_pages, const taper_plan_options* opts, HostPlan* out, std::string* err);
+
+// The general form: sequence s sees its prefix and then the private segments seg_len[seg_start[s] .. seg_start[s+1]),
+// each on pages of its own (suffix_len / n_suffix_pages of the plan are then totals over the segments).
+int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int32_t* block_table, int bt_row_stride,
+                             const int32_t* branch_group, const int32_t* prefix_len, const int32_t* seg_start,
+                             const int32_t* seg_len, int64_t n_pool_pages, const taper_plan_options* opts,
+                             HostPlan* out, std::string* err);
 
 int validate_config(const taper_attn_config& cfg, std::string* err);
 
