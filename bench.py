@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="mixed", choices=["mixed", "irp_off", "long", "tiny", "sweep", "controller"])
+    ap.add_argument("--workload", default="mixed", choices=["mixed", "irp_off", "long", "tiny", "sweep", "controller", "phase"])
     ap.add_argument("--layers", type=int, default=0, help="layers per step (0 = workload default)")
     ap.add_argument("--target-workgroups", type=int, default=0)
     ap.add_argument("--shared-cost-pct", type=int, default=0)
@@ -256,6 +256,90 @@ def run_controller(args):
     }
 
 
+def run_phase(args):
+    """The two steps around the parallel phase, on the admission-sweep batch at full width (96 serial requests
+    + 32 requests with 17 branches): (i) KV append of one token per sequence (640 sequences) and (ii) the
+    first reduce step -- every parallel request has become ONE sequence that attends to its prefix, all 17
+    branches' private pages in order, and its own reduce tokens (section 3.1) -- next to the serial requests."""
+    import torch
+
+    from paper_2605_06914_amd import Context, append_slots
+    from taper_inputs import reduce_structure, structure_config5
+    from taper_inputs.generators import QWEN as sh
+
+    dev = torch.device("cuda:0")
+    n_layers = args.layers or 8
+    par = structure_config5(16)
+    rng = np.random.Generator(np.random.PCG64(20260507))
+    seg = reduce_structure(par, z_len=[0] * 96 + [int(x) for x in rng.integers(1, 65, size=32)], seed=20260508)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20260509)
+    kvs = [torch.empty(par.n_pool_pages * sh.page_elems, device=dev, dtype=torch.bfloat16).normal_(generator=gen)
+           for _ in range(n_layers)]
+    ctx = Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, device=0)
+    # ---- append: one token for each of the 640 sequences of the parallel step
+    S = par.n_seqs
+    bt = np.concatenate([par.block_table, np.full((S, 1), -1, np.int32)], axis=1)
+    used = np.zeros(par.n_pool_pages, bool)
+    used[bt[bt >= 0]] = True
+    fresh = list(np.flatnonzero(~used))
+    for s in np.flatnonzero(par.suffix_len % 16 == 0):
+        bt[s, -(-int(par.prefix_len[s]) // 16) + int(par.suffix_len[s]) // 16] = fresh.pop()
+    slots, opens = append_slots(bt, par.prefix_len, np.arange(S + 1, dtype=np.int32), par.suffix_len, 16, par.n_pool_pages)
+    slots_dev = torch.from_numpy(slots).to(dev)
+    k_new = torch.randn((S, sh.n_kv_heads, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16)
+    v_new = torch.randn((S, sh.n_kv_heads, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    stream = torch.cuda.current_stream()
+    for _ in range(5):
+        for l in range(n_layers):
+            ctx.kv_append(k_new, v_new, slots_dev, kvs[l], S)
+    reps = 50
+    ev[0].record(stream)
+    for _ in range(reps):
+        for l in range(n_layers):
+            ctx.kv_append(k_new, v_new, slots_dev, kvs[l], S)
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    append_us = ev[0].elapsed_time(ev[1]) * 1e3 / (reps * n_layers)
+    append_bytes = 2 * S * sh.n_kv_heads * sh.head_dim * 2 * 2  # rows read and written
+    # ---- reduce step
+    Sr = seg.n_seqs
+    qs = [torch.randn((Sr, sh.n_q_heads, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16) for _ in range(n_layers)]
+    outs = [torch.zeros_like(q) for q in qs]
+    plan = ctx.plan_build_segments(seg.block_table, seg.branch_group, seg.prefix_len, seg.seg_start, seg.seg_len,
+                                   seg.n_pool_pages)
+    kt = {"decode_us": 0.0, "decode_us_min": 0.0}
+    for l in range(n_layers):
+        r = ctx.kernel_times(plan, qs[l], kvs[l], outs[l], warmup=5, iters=args.kernel_iters)
+        for k in kt:
+            kt[k] += r[k] / n_layers
+    probe = ctx.step_latency_probe(plan, qs, kvs, outs, warmup=2, iters=max(5, args.steps))
+    e = plan.export()
+    plan.free()
+    ctx.close()
+    kv_bytes = seg.logical_tokens * sh.kv_bytes_per_token  # nothing is shared in this step: every sequence is alone in its request
+    alg = kv_bytes + 2 * Sr * sh.n_q_heads * sh.head_dim * 2
+    achieved = alg / (kt["decode_us"] * 1e-6) / 1e9
+    return {
+        "metric": "decode_step_attention_effective_kv_bandwidth", "value": round(probe.gbps_unique, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(probe.us_median / 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"first reduce step after the admission-sweep batch's parallel phase (96 serial + 32 reduce "
+                               f"sequences over prefix + 17 branches + reduce tokens) x {n_layers} layers, and the KV append "
+                               f"of the parallel step before it (640 sequences)",
+                   "n_layers": n_layers, "n_seqs": Sr, "segments": int(len(seg.seg_len)), "tokens": seg.logical_tokens},
+        "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "bytes_per_launch": alg,
+                     "avg_launch_us": round(kt["decode_us"], 2), "kernel_us": {k: round(v, 2) for k, v in kt.items()},
+                     "work_items": int(e["items"].shape[0])},
+        "kv_append": {"kernel": "kv_append_kernel", "sequences": S, "us_per_launch": round(append_us, 2),
+                      "bytes_per_launch": append_bytes, "pages_opened": int(opens.sum()),
+                      "note": "launch-bound: 2.6 MB read and 2.6 MB written per launch"},
+        "cpu_baseline": None,
+    }
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -276,6 +360,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}}))
+        return
+    if args.workload == "phase":
+        print(json.dumps(run_phase(args)))
         return
     if args.workload == "controller":
         print(json.dumps(run_controller(args)))
