@@ -181,12 +181,18 @@ DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const i
 #pragma unroll
                 for (int u = 0; u < U; ++u) o[k][u] = (f32x4)(0.f);
                 if (e + k < e1) {
+                    // the entry is the same for every lane: its rows' base address goes into scalar
+                    // registers and each load needs only a 32-bit per-lane offset
                     const taper_merge_entry me = merge_entry(a, mm, e + k);
-                    const int64_t rowi = (int64_t)me.first_row + (int64_t)hk * me.rows_per_head + (okr ? j : 0);
-                    const float2 v = coherent_load2((const float*)(a.ws_ml + rowi));
+                    const int64_t row0 = (int64_t)__builtin_amdgcn_readfirstlane(me.first_row) +
+                                         (int64_t)hk * __builtin_amdgcn_readfirstlane(me.rows_per_head);
+                    const float* op = a.ws_o + row0 * D;
+                    const float2* mp = a.ws_ml + row0;
+                    const unsigned jo = okr ? j : 0;
+                    const float2 v = coherent_load2((const float*)(mp + jo));
                     if (okr) ml[k] = v;
 #pragma unroll
-                    for (int u = 0; u < U; ++u) o[k][u] = coherent_load4(a.ws_o + rowi * D + 4 * (c0 + LPR * u));
+                    for (int u = 0; u < U; ++u) o[k][u] = coherent_load4(op + (jo * D + 4u * (c0 + LPR * u)));
                 }
             }
             float mn = M;
@@ -387,7 +393,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
 // launch.
 template <int D>
 DEV void private_items(const StepArgs& a, int it0, const int it1, const int hk, PrivateSmem<D>& sm) {
-    const int wgs_per_head = gridDim.x / a.n_kv_heads;
+    const int wgs_per_head = a.n_parts_shared + a.n_parts_private;  // = gridDim.x / n_kv_heads
     for (;;) {
         int it = it0;
         if (it0 < it1) {
@@ -432,22 +438,24 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
     constexpr int QE = SharedSmem<D>::QE, VQ = SharedSmem<D>::VQ, PAGE_LDS = SharedSmem<D>::PAGE_LDS,
                   BUF = SharedSmem<D>::BUF;
     __bf16* lds = sm.kv;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n = lane & 15, qd = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int Hkv = a.n_kv_heads, g = a.gqa;
     const __bf16* __restrict__ kvb = (const __bf16*)a.kv;
     const int64_t page_elems = 2LL * Hkv * TILE;
     const float c = a.scale_log2e;
-    const int se = tid * 8;                       // staging: this thread's element offset inside a tile
-    const bool stager = se < TILE;
-    const int sv = (se / QE) * VQ + se % QE;      // ... and inside the padded V tile in LDS
-    const int koff = lane * 8;
-    const int voff = TILE + qd * VQ + n * 4;
 
     const int it0 = a.part_start[part], it1 = a.part_start[part + 1];
     for (int it = it0; it < it1; ++it) {
+        // per-lane constants are derived inside the loop from an opaque thread id, so that they are
+        // not kept alive across the item's end (the merge wants the registers)
+        const int tid = opaque(threadIdx.x);
+        const int lane = tid & 63;
+        const int n = lane & 15, qd = lane >> 4;
+        const int se = tid * 8;                       // staging: this thread's element offset inside a tile
+        const bool stager = se < TILE;
+        const int sv = (se / QE) * VQ + se % QE;      // ... and inside the padded V tile in LDS
+        const int koff = lane * 8;
+        const int voff = TILE + qd * VQ + n * 4;
         const taper_work_item item = a.items[it];
         const int32_t* __restrict__ row = a.bt + (int64_t)item.seq0 * a.bt_stride + item.page0;
         const int n_tok = item.n_tokens;
@@ -607,7 +615,7 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
         const long long t_m0 = wall_clock64();
 #endif
         for (int b = wave; b < item.n_branch; b += 4)
-            if (sm.last[b]) merge_rows<D, D / 32, 5>(a, sm.meta, item.seq0 + b, hk, sm.meta.ms[b], sm.meta.ms[b + 1], lane, 64);
+            if (sm.last[b]) merge_rows<D, D / 32, (NTW == 1 ? 6 : 8)>(a, sm.meta, item.seq0 + b, hk, sm.meta.ms[b], sm.meta.ms[b + 1], lane, 64);
 #ifdef TAPER_WG_TRACE
         __syncthreads();
         if (tid == 0 && a.lse) ((long long*)a.lse)[4 * blockIdx.x + 3] += wall_clock64() - t_m0;
