@@ -141,6 +141,9 @@ typedef struct {
     int32_t shared_item_cost;  /* 0 = default (800): fixed cost of a shared-prefix item, in private
                                   tokens' streaming time                                       */
     int32_t private_item_cost; /* 0 = default (128): fixed cost of a private item, same unit      */
+    int32_t private_merge_cost; /* 0 = default (192 when the step has shared-prefix work, else none),
+                                  -1 = none: extra cost of the private item that ends a sequence
+                                  (as a rule it delivers the last partial and merges)           */
     int32_t pool_pct;          /* 0 = default (25 when the step has shared-prefix work, else none):
                                   percentage of the private tokens that no share owns; workgroups
                                   that finish their share take them, an item at a time, so the

@@ -48,6 +48,7 @@ namespace {
 
 struct Segment {
     int32_t seq0, n_branch, page0, n_tokens, kind;
+    int32_t ends_seq = 0;  // private: the last tokens of its sequence in plan order (whoever streams them usually merges)
 };
 
 // Cost model of a workgroup share, in units of one private token's streaming time: an item of
@@ -55,6 +56,7 @@ struct Segment {
 // streaming its tokens (query load, pipeline fill, partial rows, arrival, merges).
 struct Cost {
     int64_t per_token_pct, fixed;
+    int64_t merge = 0;  // extra cost of the item that ends a sequence: it arrives last as a rule and merges the partials
 };
 
 // Cuts `segs` into workgroup shares of about `quota` cost units, at multiples of `blk` tokens
@@ -95,6 +97,7 @@ int partition_fill(const std::vector<Segment>& segs, int64_t quota, int blk, con
             fill += cost.fixed + take * blk_cost;
             off += take;
             remaining -= take;
+            if (remaining == 0 && s.ends_seq) fill += cost.merge;
             if (fill >= quota) {
                 ++part;
                 fill = 0;
@@ -340,6 +343,7 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
             p.tokens_unique += p.suffix_len[s];
             for (int k = seg_start[s]; k < seg_start[s + 1]; ++k)
                 if (seg_len[k] > 0) priv.push_back({s, 1, p.seg_page0[k], seg_len[k], 1});
+            if (!priv.empty() && priv.back().seq0 == s) priv.back().ends_seq = 1;
         }
     }
 
@@ -352,14 +356,16 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
     for (const Segment& s : shared) widest = std::max(widest, (s.n_branch * g + 15) / 16);
     const Cost cost_shared = {opts && opts->shared_cost_pct > 0 ? opts->shared_cost_pct : (widest <= 4 ? 160 : 200),
                               opts && opts->shared_item_cost > 0 ? opts->shared_item_cost : 800};
-    const Cost cost_priv = {100, opts && opts->private_item_cost > 0 ? opts->private_item_cost : 128};
+    const Cost cost_priv = {100, opts && opts->private_item_cost > 0 ? opts->private_item_cost : 128,
+                            opts && opts->private_merge_cost != 0 ? std::max(0, opts->private_merge_cost)
+                                                                  : (shared.empty() ? 0 : 192)};
     const int64_t shared_tail_discount = 3;  // blocks: about what merging a request's branches costs
     int64_t cost_total = 0;
     for (const Segment& s : shared) {
         cost_total += cost_shared.fixed + (int64_t)s.n_tokens * cost_shared.per_token_pct / 100;
     }
     for (const Segment& s : priv) {
-        cost_total += cost_priv.fixed + s.n_tokens;
+        cost_total += cost_priv.fixed + s.n_tokens + (s.ends_seq ? cost_priv.merge : 0);
     }
     const int parts_total = std::max(1, target_wgs / cfg.n_kv_heads);
     // ---- the pool: private tokens no share owns.  No cost model predicts the shares' running times
@@ -380,15 +386,16 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
             Segment& s = priv.back();
             if (s.n_tokens <= want + kPrivateBlockTokens) {  // the whole segment
                 want -= s.n_tokens;
-                cost_total -= cost_priv.fixed + s.n_tokens;
+                cost_total -= cost_priv.fixed + s.n_tokens + (s.ends_seq ? cost_priv.merge : 0);
                 pool.push_back(s);
                 priv.pop_back();
             } else {  // its tail, from a block boundary
                 const int keep = (int)((s.n_tokens - want + kPrivateBlockTokens - 1) / kPrivateBlockTokens * kPrivateBlockTokens);
                 if (keep < s.n_tokens) {
-                    pool.push_back({s.seq0, s.n_branch, s.page0 + keep / 16, s.n_tokens - keep, s.kind});
-                    cost_total -= s.n_tokens - keep;
+                    pool.push_back({s.seq0, s.n_branch, s.page0 + keep / 16, s.n_tokens - keep, s.kind, s.ends_seq});
+                    cost_total -= s.n_tokens - keep + (s.ends_seq ? cost_priv.merge : 0);
                     s.n_tokens = keep;
+                    s.ends_seq = 0;
                 }
                 want = 0;
             }
