@@ -176,6 +176,43 @@ def test_same_plan_replayed(ctx_qwen):
         assert np.array_equal(bits[0], x)
 
 
+def test_many_partials_per_sequence(ctx_qwen):
+    """Very fine shares: a sequence's partials number in the hundreds, far more than one merge round holds
+    and more than the item-start prefetch of merge entries covers (the rest is fetched during the merge)."""
+    reqs = [(9000, [0]), (6000, [3, 0, 70, 1, 200, 16, 5, 9, 130, 2, 31, 64, 8, 4, 77, 12]), (40, [0])]
+    b = fill_values_numpy(structure_custom(QWEN, reqs, seed=109))
+    st = b.structure
+    plan = ctx_qwen.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages,
+                               target_workgroups=8192, pool_pct=-1)
+    e = plan.export()
+    per_seq = np.diff(e["merge_start"])
+    plan.free()
+    assert per_seq[0] > 128 and per_seq[1:17].sum() > 128 and per_seq[1] > 8
+    ref, ref_lse = run_oracle(b)
+    got, lse, _ = run_gpu(ctx_qwen, b, target_workgroups=8192, pool_pct=-1)
+    assert_parity(got, ref, f"{int(per_seq.max())} partials per sequence")
+    assert np.max(np.abs(lse - ref_lse)) <= 2e-3
+
+
+@pytest.mark.parametrize("hq,hkv,d", [(16, 1, 128), (8, 8, 64), (6, 2, 128), (32, 8, 64), (64, 4, 128)])
+def test_other_head_shapes(hq, hkv, d):
+    """Group sizes 1, 3, 4, 16 (the largest supported) and both head dims, on a ragged batch with wide requests."""
+    from paper_2605_06914_amd import Context
+
+    sh = AttnShape(hq, hkv, d, 16)
+    reqs = RAGGED + [(333, [int(x) for x in np.random.default_rng(hq).integers(0, 60, size=21)])]
+    b = fill_values_numpy(structure_custom(sh, reqs, seed=110 + hq))
+    ctx = Context(hq, hkv, d, device=0)
+    try:
+        ref, ref_lse = run_oracle(b)
+        for kw in ({}, dict(target_workgroups=2048)):
+            got, lse, _ = run_gpu(ctx, b, **kw)
+            assert_parity(got, ref, f"shape Hq{hq} Hkv{hkv} D{d} {kw}")
+            assert np.max(np.abs(lse - ref_lse)) <= 2e-3
+    finally:
+        ctx.close()
+
+
 def test_sibling_independence(ctx_qwen):
     """Lemma 1: which siblings share the step must not change a branch's output
     (beyond summation order; the prefix partial is computed per row, so it is in
