@@ -427,7 +427,7 @@ def main():
     e = plan.export()
     F = {n: i for i, n in enumerate(e["item_fields"])}
     tok_shared = int(e["items"][e["items"][:, F["kind"]] == 0, F["n_tokens"]].sum())
-    tok_private = int(e["items"][e["items"][:, F["kind"]] == 1, F["n_tokens"]].sum())
+    tok_private = int(e["items"][e["items"][:, F["kind"]] >= 1, F["n_tokens"]].sum())
     kt = {"decode_us": 0.0, "decode_us_min": 0.0}
     n_kt = min(n_layers, 8)
     for l in range(n_kt):

@@ -94,7 +94,8 @@ typedef struct {
     int32_t n_tokens;  /* valid tokens in the chunk (>= 1)                          */
     int32_t part_base; /* first partial row; row of (kv head hk, branch b, head-in-group j)
                           = part_base + hk * n_branch * gqa + b * gqa + j           */
-    int32_t kind;      /* 0 = shared prefix of a parallel request, 1 = private      */
+    int32_t kind;      /* 0 = shared prefix of a parallel request, 1 = private, 2 = private
+                          and the sequence's only item (result written directly, no partial) */
     int32_t part;      /* workgroup share this item belongs to; n_parts for pool items */
     int32_t merge0;    /* merge_start[seq0]: where the merge entries of the item's sequences begin */
 } taper_work_item;

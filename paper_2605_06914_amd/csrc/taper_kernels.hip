@@ -278,7 +278,9 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
         const int n_tok = item.n_tokens;
         const int n_pages = (n_tok + 15) >> 4;
         const int n_blocks = (n_tok + 31) >> 5;
-        const MetaRegs mr = meta_load(a, item, threadIdx.x);
+        const bool sole = item.kind == 2;  // the sequence's whole context: no partial, no arrival, no merge
+        MetaRegs mr = {};
+        if (!sole) mr = meta_load(a, item, threadIdx.x);
 
         bf16x8 qf[KS];
         {
@@ -349,7 +351,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
             for (int dt = 0; dt < DT; ++dt) *(f32x4*)&sm_o[wave][n][16 * dt + 4 * qd] = O[dt];
         }
         __syncthreads();
-        meta_store(sm.meta, mr, 1, threadIdx.x);  // (after the barrier: nobody still merges the previous item)
+        if (!sole) meta_store(sm.meta, mr, 1, threadIdx.x);  // (after the barrier: nobody still merges the previous item)
         for (int idx = threadIdx.x; idx < g * (D / 4); idx += 256) {
             const int r = idx / (D / 4), d4 = idx % (D / 4);
             float mw[4], M = -INFINITY;
@@ -366,9 +368,22 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
                 L += wg * sm_ml[w][r].y;
                 acc += wg * *(const f32x4*)&sm_o[w][r][4 * d4];
             }
+            if (sole) {
+                const int h = hk * g + r;
+                const f32x4 res = acc * (1.0f / L);
+                *(bf16x4*)((__bf16*)a.out + ((int64_t)item.seq0 * a.n_q_heads + h) * D + 4 * d4) = __builtin_convertvector(res, bf16x4);
+#ifndef TAPER_WG_TRACE
+                if (a.lse && d4 == 0) a.lse[(int64_t)item.seq0 * a.n_q_heads + h] = (M + __log2f(L)) * 0.6931471805599453f;
+#endif
+                continue;
+            }
             const int64_t slot = (int64_t)item.part_base + hk * g + r;
             coherent_store4(a.ws_o + slot * D + 4 * d4, acc);
             if (d4 == 0) coherent_store2((float*)(a.ws_ml + slot), M, L);
+        }
+        if (sole) {
+            __syncthreads();  // the combine buffers are free for the next item
+            return;
         }
         // publish the partial; whoever completes the sequence's set merges it
         stores_done();

@@ -451,7 +451,11 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
         p.merge_start[s + 1] = p.merge_start[s] + (int32_t)per_seq[s].size();
         p.merge.insert(p.merge.end(), per_seq[s].begin(), per_seq[s].end());
     }
-    for (taper_work_item& it : p.items) it.merge0 = p.merge_start[it.seq0];
+    for (taper_work_item& it : p.items) {
+        it.merge0 = p.merge_start[it.seq0];
+        // a private item that is its sequence's whole context needs no partial rows: the kernel writes the result
+        if (it.kind == 1 && p.merge_start[it.seq0 + 1] - p.merge_start[it.seq0] == 1) it.kind = 2;
+    }
     return TAPER_OK;
 }
 

@@ -142,15 +142,17 @@ def check_plan_against_oracle(st, **kw):
     pool_cap = max(32, (kw.get("pool_item_tokens", 0) or 512) // 32 * 32)
     assert np.all(items[ps[-1] :, F["n_tokens"]] <= pool_cap)
     nsh = e["n_parts_shared"]
-    assert np.all(items[: ps[nsh], F["kind"]] == 0) and np.all(items[ps[nsh] :, F["kind"]] == 1)
+    assert np.all(items[: ps[nsh], F["kind"]] == 0) and np.all(items[ps[nsh] :, F["kind"]] >= 1)
     rows = items[:, F["n_branch"]].astype(np.int64) * g * sh.n_kv_heads
     assert np.array_equal(items[:, F["part_base"]], np.concatenate([[0], np.cumsum(rows)[:-1]]))
     assert e["n_partial_rows"] == rows.sum()
     ms, merge = e["merge_start"], e["merge"]
     for s in range(st.n_seqs):
-        mine = [(int(it[F["part_base"]]) + (s - int(it[F["seq0"]])) * g, int(it[F["n_branch"]]) * g)
-                for it in items if it[F["seq0"]] <= s < it[F["seq0"]] + it[F["n_branch"]]]
+        its = [it for it in items if it[F["seq0"]] <= s < it[F["seq0"]] + it[F["n_branch"]]]
+        mine = [(int(it[F["part_base"]]) + (s - int(it[F["seq0"]])) * g, int(it[F["n_branch"]]) * g) for it in its]
         assert [tuple(x) for x in merge[ms[s] : ms[s + 1]]] == mine
+        # kind 2 marks exactly the private items that are their sequence's only item
+        assert all((int(it[F["kind"]]) == 2) == (len(its) == 1 and it[F["n_branch"]] == 1) for it in its)
     plan.free()
     return e
 
@@ -175,7 +177,7 @@ def test_plan_options(kw):
     if kw.get("pool_pct") == 90:
         F = {n: i for i, n in enumerate(e["item_fields"])}
         it = e["items"]
-        priv = it[it[:, F["kind"]] == 1]
+        priv = it[it[:, F["kind"]] >= 1]
         pooled = it[e["part_start"][-1] :, F["n_tokens"]].sum()
         assert 0.85 * priv[:, F["n_tokens"]].sum() <= pooled <= 0.9 * priv[:, F["n_tokens"]].sum() + 64
 
