@@ -72,6 +72,7 @@ int partition_fill(const std::vector<Segment>& segs, int64_t quota, int blk, con
     const int64_t blk_cost = std::max<int64_t>(1, blk * cost.per_token_pct / 100);
     // a piece is only worth an item of its own if its streaming outweighs the item's fixed cost
     const int64_t min_blocks = std::max<int64_t>(1, (cost.fixed + blk_cost - 1) / blk_cost);
+    const int64_t cap = std::max<int64_t>(1, (quota - cost.fixed) / blk_cost);  // blocks of an item with a share to itself
     int part = 0;
     int64_t fill = 0;
     for (const Segment& s : segs) {
@@ -84,6 +85,17 @@ int partition_fill(const std::vector<Segment>& segs, int64_t quota, int blk, con
                 continue;
             }
             int64_t take = std::min(remaining, std::max<int64_t>(room, 1));
+            // A segment much shorter than a share is not cut: cutting would turn one item (which may be its
+            // sequence's only one and then needs no partial rows at all) into two with a merge.  It goes
+            // whole into this share if at least half of it fits, else into the next.
+            if (off == 0 && take < remaining && remaining * 4 <= cap) {
+                if (fill > 0 && room * 2 < remaining) {
+                    ++part;
+                    fill = 0;
+                    continue;
+                }
+                take = remaining;
+            }
             if (remaining - take > 0 && remaining - take < min_blocks) take = remaining;  // no sliver left behind
             taper_work_item it;
             std::memset(&it, 0, sizeof it);
