@@ -95,7 +95,8 @@ typedef struct {
     int32_t part_base; /* first partial row; row of (kv head hk, branch b, head-in-group j)
                           = part_base + hk * n_branch * gqa + b * gqa + j           */
     int32_t kind;      /* 0 = shared prefix of a parallel request, 1 = private, 2 = private
-                          and the sequence's only item (result written directly, no partial) */
+                          and the sequence's only item (result written directly, no partial),
+                          3 = like 2 and run by a single wave (runs of short sequences)      */
     int32_t part;      /* workgroup share this item belongs to; n_parts for pool items */
     int32_t merge0;    /* merge_start[seq0]: where the merge entries of the item's sequences begin */
 } taper_work_item;
@@ -145,6 +146,9 @@ typedef struct {
     int32_t private_merge_cost; /* 0 = default (192 when the step has shared-prefix work, else none),
                                   -1 = none: extra cost of the private item that ends a sequence
                                   (as a rule it delivers the last partial and merges)           */
+    int32_t solo_item_tokens;  /* 0 = default (512), -1 = never: sequences that are one item of at most this
+                                  many tokens are run by single waves, four side by side, where a share
+                                  holds at least 4 of them in a row                               */
     int32_t pool_pct;          /* 0 = default (25 when the step has shared-prefix work, else none):
                                   percentage of the private tokens that no share owns; workgroups
                                   that finish their share take them, an item at a time, so the

@@ -259,12 +259,15 @@ struct PrivateSmem {
 };
 
 // One private item: a chunk of one sequence's own tokens, for kv head hk.
-template <int D>
+// SOLO: the item is run by the calling wave alone (short sequences that are a single item:
+// four of them proceed side by side in a workgroup, with no barrier and no LDS); otherwise the
+// four waves of the workgroup share the item's blocks.
+template <int D, bool SOLO>
 DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem<D>& sm) {
     constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D;
     auto& sm_o = sm.o;
     auto& sm_ml = sm.ml;
-    const int lane = threadIdx.x & 63;
+    const int lane = opaque(threadIdx.x) & 63;  // (opaque: per-lane constants are recomputed per item, not kept for the whole kernel)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15, qd = lane >> 4;
     const int Hkv = a.n_kv_heads, g = a.gqa;
@@ -278,7 +281,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
         const int n_tok = item.n_tokens;
         const int n_pages = (n_tok + 15) >> 4;
         const int n_blocks = (n_tok + 31) >> 5;
-        const bool sole = item.kind == 2;  // the sequence's whole context: no partial, no arrival, no merge
+        const bool sole = SOLO || item.kind >= 2;  // the sequence's whole context: no partial, no arrival, no merge
         MetaRegs mr = {};
         if (!sole) mr = meta_load(a, item, threadIdx.x);
 
@@ -330,17 +333,33 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
         };
 
         KVRegs<D> r0, r1;
-        int b = wave;
+        constexpr int STEP = SOLO ? 1 : 4;  // blocks wave, wave + 4, ... of a shared item; all blocks of a solo one
+        int b = SOLO ? 0 : wave;
         if (b < n_blocks) load_block(b, r0);
         while (b < n_blocks) {
-            const int b1 = b + 4;
+            const int b1 = b + STEP;
             if (b1 < n_blocks) load_block(b1, r1);
             compute_block(b, r0);
             if (b1 >= n_blocks) break;
-            const int b2 = b1 + 4;
+            const int b2 = b1 + STEP;
             if (b2 < n_blocks) load_block(b2, r0);
             compute_block(b1, r1);
             b = b2;
+        }
+
+        if constexpr (SOLO) {  // this wave holds the whole result: normalise and write it
+            l = sum_lane_groups(l);
+            if (n < g) {
+                const int h = hk * g + n;
+                const float inv = 1.0f / l;
+                __bf16* orow = (__bf16*)a.out + ((int64_t)item.seq0 * a.n_q_heads + h) * D;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) *(bf16x4*)(orow + 16 * dt + 4 * qd) = __builtin_convertvector(O[dt] * inv, bf16x4);
+#ifndef TAPER_WG_TRACE
+                if (a.lse && qd == 0) a.lse[(int64_t)item.seq0 * a.n_q_heads + h] = (m + __log2f(l)) * 0.6931471805599453f;
+#endif
+            }
+            return;
         }
 
         // combine the four waves' states
@@ -425,7 +444,16 @@ DEV void private_items(const StepArgs& a, int it0, const int it1, const int hk, 
             }
             it = a.pool_first + i;
         }
-        private_item<D>(a, it, hk, sm);
+        if (a.items[it].kind == 3) {  // a run of solo items of this share: dealt to the waves, no barrier inside
+            int end = it + 1;
+            while (end < it1 && a.items[end].kind == 3) ++end;
+            const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+            for (int k = it + wave; k < end; k += 4) private_item<D, true>(a, k, hk, sm);
+            it0 = end;
+            __syncthreads();
+            continue;
+        }
+        private_item<D, false>(a, it, hk, sm);
     }
 }
 

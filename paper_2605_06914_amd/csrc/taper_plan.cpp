@@ -468,6 +468,21 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
         // a private item that is its sequence's whole context needs no partial rows: the kernel writes the result
         if (it.kind == 1 && p.merge_start[it.seq0 + 1] - p.merge_start[it.seq0] == 1) it.kind = 2;
     }
+    // Runs of short such items inside one share are worked on by single waves, four items side by side
+    // (a 128-token item gives a wave one block to do when four waves share it: all latency, no streaming).
+    const int solo_tokens = opts && opts->solo_item_tokens != 0 ? opts->solo_item_tokens : 512;
+    const int n_parts_all = p.n_parts_shared + p.n_parts_private;
+    for (int part = p.n_parts_shared; part < n_parts_all && solo_tokens > 0; ++part) {
+        int i = p.part_start[part];
+        const int end = p.part_start[part + 1];
+        while (i < end) {
+            int j = i;
+            while (j < end && p.items[j].kind == 2 && p.items[j].n_tokens <= solo_tokens) ++j;
+            if (j - i >= kSoloMinRun)
+                for (int k = i; k < j; ++k) p.items[k].kind = 3;
+            i = std::max(j, i + 1);
+        }
+    }
     return TAPER_OK;
 }
 

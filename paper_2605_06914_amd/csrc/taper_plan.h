@@ -11,6 +11,7 @@ namespace taper {
 
 constexpr int kPrivateBlockTokens = 32;  // tokens one wave of the private kernel consumes per iteration
 constexpr int kSharedBlockTokens = 64;   // tokens one workgroup of the shared kernel stages per iteration
+constexpr int kSoloMinRun = 4;           // shortest run of short single-item sequences handed to single waves
 constexpr int kMaxRowTilesPerItem = 12;  // 16-row query tiles one shared-kernel workgroup can hold (4 waves x 3)
 
 struct HostPlan {

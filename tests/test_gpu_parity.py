@@ -213,6 +213,30 @@ def test_other_head_shapes(hq, hkv, d):
         ctx.close()
 
 
+@pytest.mark.parametrize("kw", [{}, dict(solo_item_tokens=-1), dict(solo_item_tokens=64), dict(target_workgroups=64)])
+def test_many_short_sequences(ctx_qwen, kw):
+    """Batches of short serial requests: each sequence is one item whose result the kernel writes directly
+    (no partial rows), and runs of them are worked on by single waves, four side by side."""
+    rng = np.random.default_rng(12)
+    reqs = [(int(n), [0]) for n in rng.integers(1, 300, size=700)] + [(2000, [0]), (5, [3, 0])] + \
+           [(0, [int(n)]) for n in rng.integers(1, 200, size=40)]
+    b = fill_values_numpy(structure_custom(QWEN, reqs, seed=111))
+    st = b.structure
+    plan = ctx_qwen.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages, **kw)
+    e = plan.export()
+    plan.free()
+    kinds = np.bincount(e["items"][:, e["item_fields"].index("kind")], minlength=4)
+    assert kinds[2] + kinds[3] >= 700
+    if kw.get("solo_item_tokens", 0) == -1:
+        assert kinds[3] == 0
+    elif kw.get("solo_item_tokens", 0) == 0:
+        assert kinds[3] > 100
+    ref, ref_lse = run_oracle(b)
+    got, lse, _ = run_gpu(ctx_qwen, b, **kw)
+    assert_parity(got, ref, f"short sequences {kw} kinds {kinds.tolist()}")
+    assert np.max(np.abs(lse - ref_lse)) <= 2e-3
+
+
 def test_sibling_independence(ctx_qwen):
     """Lemma 1: which siblings share the step must not change a branch's output
     (beyond summation order; the prefix partial is computed per row, so it is in
