@@ -149,6 +149,10 @@ typedef struct {
     int32_t solo_item_tokens;  /* 0 = default (512), -1 = never: sequences that are one item of at most this
                                   many tokens are run by single waves, four side by side, where a share
                                   holds at least 4 of them in a row                               */
+    int32_t min_share_tokens;  /* a small step is cut into fewer shares than target_workgroups allows
+                                  rather than into shares below this size.  0 = default: 256, or 1/16
+                                  of the longest private segment if that is more (keeps the partials
+                                  of one sequence to about 16)                                   */
     int32_t pool_pct;          /* 0 = default (25 when the step has shared-prefix work, else none):
                                   percentage of the private tokens that no share owns; workgroups
                                   that finish their share take them, an item at a time, so the

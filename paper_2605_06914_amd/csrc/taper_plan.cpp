@@ -414,7 +414,13 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
         }
         std::reverse(pool.begin(), pool.end());
     }
-    int64_t quota = std::max<int64_t>(kSharedBlockTokens, (cost_total + parts_total - 1) / parts_total);
+    // A small step is not cut as finely as the grid allows: below a few hundred tokens per share the
+    // time goes into the item ends, and a sequence cut into many partials pays a merge round per eight.
+    int64_t longest = 0;
+    for (const Segment& s : priv) longest = std::max<int64_t>(longest, s.n_tokens);
+    const int64_t min_share =
+        (opts && opts->min_share_tokens > 0 ? opts->min_share_tokens : std::max<int64_t>(256, longest / 16)) + cost_priv.fixed;
+    int64_t quota = std::max<int64_t>(std::max<int64_t>(kSharedBlockTokens, min_share), (cost_total + parts_total - 1) / parts_total);
     for (;;) {  // never more shares than asked for: an extra one would run after all the others
         p.items.clear();
         p.n_parts_shared = partition_even(shared, quota, kSharedBlockTokens, cost_shared, shared_tail_discount, 0, &p.items);

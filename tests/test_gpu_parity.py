@@ -54,14 +54,15 @@ RAGGED = [(37, [0]), (50, [0, 7, 16, 21]), (16, [1]), (700, [0, 33, 64, 65, 129,
           (0, [45]), (31, [31, 32, 33]), (64, [0, 0]), (129, [1] * 9)]
 
 
-@pytest.mark.parametrize("share,target", [(True, 0), (False, 0), (True, 8), (True, 4096)])
+@pytest.mark.parametrize("share,target", [(True, 0), (False, 0), (True, 8), (True, 4096), (True, -4096)])
 def test_ragged_qwen_shape(ctx_qwen, share, target):
     """Several tiles, partial pages, prefixes ending mid-page, empty branches, a
     suffix-only sequence, one-token context; also under very coarse and very fine
     workgroup shares."""
     b = fill_values_numpy(structure_custom(QWEN, RAGGED, seed=101))
     ref, ref_lse = run_oracle(b)
-    got, lse, _ = run_gpu(ctx_qwen, b, share_prefix=share, target_workgroups=target)
+    kw = dict(target_workgroups=target) if target >= 0 else dict(target_workgroups=-target, min_share_tokens=1)
+    got, lse, _ = run_gpu(ctx_qwen, b, share_prefix=share, **kw)
     assert_parity(got, ref, f"ragged share={share} target={target}")
     assert np.max(np.abs(lse - ref_lse)) <= 2e-3
 
@@ -183,13 +184,13 @@ def test_many_partials_per_sequence(ctx_qwen):
     b = fill_values_numpy(structure_custom(QWEN, reqs, seed=109))
     st = b.structure
     plan = ctx_qwen.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages,
-                               target_workgroups=8192, pool_pct=-1)
+                               target_workgroups=8192, pool_pct=-1, min_share_tokens=1)
     e = plan.export()
     per_seq = np.diff(e["merge_start"])
     plan.free()
     assert per_seq[0] > 128 and per_seq[1:17].sum() > 128 and per_seq[1] > 8
     ref, ref_lse = run_oracle(b)
-    got, lse, _ = run_gpu(ctx_qwen, b, target_workgroups=8192, pool_pct=-1)
+    got, lse, _ = run_gpu(ctx_qwen, b, target_workgroups=8192, pool_pct=-1, min_share_tokens=1)
     assert_parity(got, ref, f"{int(per_seq.max())} partials per sequence")
     assert np.max(np.abs(lse - ref_lse)) <= 2e-3
 

@@ -163,7 +163,7 @@ def test_plan_integers_match_oracle(maker):
     check_plan_against_oracle(maker())
 
 
-@pytest.mark.parametrize("kw", [dict(share_prefix=False), dict(target_workgroups=8), dict(target_workgroups=100000),
+@pytest.mark.parametrize("kw", [dict(share_prefix=False), dict(target_workgroups=8), dict(target_workgroups=100000), dict(target_workgroups=100000, min_share_tokens=1),
                                 dict(max_branches_per_item=3), dict(pool_pct=-1), dict(pool_pct=90, pool_item_tokens=64), dict(pool_pct=100, pool_item_tokens=200),
                                 dict(shared_cost_pct=300, shared_item_cost=5000, private_item_cost=1)])
 def test_plan_options(kw):
