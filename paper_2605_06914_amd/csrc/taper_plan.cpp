@@ -448,6 +448,9 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
         }
     }
     p.n_pool_items = (int)p.items.size() - p.part_start[n_parts];
+    // longest first: the launch's last claims are then the shortest items
+    std::stable_sort(p.items.begin() + p.part_start[n_parts], p.items.end(),
+                     [](const taper_work_item& x, const taper_work_item& y) { return x.n_tokens > y.n_tokens; });
 
     // ---- partial rows and merge map
     std::vector<std::vector<taper_merge_entry>> per_seq(n_seqs);
