@@ -157,8 +157,8 @@ typedef struct {
                                   percentage of the private tokens that no share owns; workgroups
                                   that finish their share take them, an item at a time, so the
                                   launch ends evenly.  -1 = none; values above 90 count as 90    */
-    int32_t pool_item_tokens;  /* 0 = default (512): size of the pool's items, rounded down to a
-                                  multiple of 32 tokens (at least 32)                            */
+    int32_t pool_item_tokens;  /* size of the pool's items, rounded down to a multiple of 32 tokens (at
+                                  least 32); 0 = default: a quarter of a share, between 512 and 1536 */
 } taper_plan_options;
 
 TAPER_API int taper_create(const taper_attn_config *cfg /* host */, taper_ctx **out_ctx);

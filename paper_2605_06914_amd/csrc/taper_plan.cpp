@@ -387,8 +387,7 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
     // Without shared-prefix work the shares are alike and end within a few percent of each other:
     // a pool would only add items.
     const int pool_pct = opts && opts->pool_pct != 0 ? std::max(0, std::min(90, opts->pool_pct)) : (shared.empty() ? 0 : 25);
-    const int pool_item_tokens =
-        std::max(kPrivateBlockTokens, (opts && opts->pool_item_tokens > 0 ? opts->pool_item_tokens : 512) / kPrivateBlockTokens * kPrivateBlockTokens);
+    const int pool_item_opt = opts && opts->pool_item_tokens > 0 ? opts->pool_item_tokens : 0;
     std::vector<Segment> pool;
     {
         int64_t tok_priv = 0;
@@ -432,6 +431,10 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
     p.part_start.assign(n_parts + 1, 0);
     for (const taper_work_item& it : p.items) p.part_start[it.part + 1]++;
     for (int i = 0; i < n_parts; ++i) p.part_start[i + 1] += p.part_start[i];
+    // size of the pool's items: a quarter of a share, between 512 and 1536 tokens, unless the caller says otherwise
+    const int pool_item_tokens = std::max<int>(
+        kPrivateBlockTokens,
+        (pool_item_opt ? pool_item_opt : (int)std::min<int64_t>(1536, std::max<int64_t>(512, quota / 4))) / kPrivateBlockTokens * kPrivateBlockTokens);
     for (const Segment& s : pool) {  // pool items follow the shares' items; their `part` is n_parts
         const int k = (s.n_tokens + pool_item_tokens - 1) / pool_item_tokens;
         const int piece = ((s.n_tokens + k - 1) / k + kPrivateBlockTokens - 1) / kPrivateBlockTokens * kPrivateBlockTokens;

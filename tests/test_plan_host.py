@@ -139,7 +139,7 @@ def check_plan_against_oracle(st, **kw):
     assert ps[0] == 0 and ps[-1] + n_pool == len(items) and np.all(np.diff(ps) >= 1)
     assert np.array_equal(items[: ps[-1], F["part"]], np.repeat(np.arange(len(ps) - 1), np.diff(ps)))
     assert np.all(items[ps[-1] :, F["part"]] == len(ps) - 1) and np.all(items[ps[-1] :, F["n_branch"]] == 1)
-    pool_cap = max(32, (kw.get("pool_item_tokens", 0) or 512) // 32 * 32)
+    pool_cap = max(32, (kw.get("pool_item_tokens", 0) or 1536) // 32 * 32)
     assert np.all(items[ps[-1] :, F["n_tokens"]] <= pool_cap)
     nsh = e["n_parts_shared"]
     assert np.all(items[: ps[nsh], F["kind"]] == 0) and np.all(items[ps[nsh] :, F["kind"]] >= 1)
