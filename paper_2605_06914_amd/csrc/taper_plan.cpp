@@ -49,6 +49,7 @@ namespace {
 struct Segment {
     int32_t seq0, n_branch, page0, n_tokens, kind;
     int32_t ends_seq = 0;  // private: the last tokens of its sequence in plan order (whoever streams them usually merges)
+    int32_t whole_seq = 0;  // private: the sequence's whole context
 };
 
 // Cost model of a workgroup share, in units of one private token's streaming time: an item of
@@ -85,10 +86,10 @@ int partition_fill(const std::vector<Segment>& segs, int64_t quota, int blk, con
                 continue;
             }
             int64_t take = std::min(remaining, std::max<int64_t>(room, 1));
-            // A segment much shorter than a share is not cut: cutting would turn one item (which may be its
-            // sequence's only one and then needs no partial rows at all) into two with a merge.  It goes
-            // whole into this share if at least half of it fits, else into the next.
-            if (off == 0 && take < remaining && remaining * 4 <= cap) {
+            // A sequence much shorter than a share is not cut: cutting would turn one item that needs no
+            // partial rows at all into two with a merge.  It goes whole into this share if at least half of
+            // it fits, else into the next.
+            if (s.whole_seq && off == 0 && take < remaining && remaining * 4 <= cap) {
                 if (fill > 0 && room * 2 < remaining) {
                     ++part;
                     fill = 0;
@@ -359,6 +360,14 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
         }
     }
 
+    {  // private segments that are their sequence's whole context
+        std::vector<int32_t> pieces(n_seqs, 0);
+        for (const Segment& s : shared)
+            for (int b = 0; b < s.n_branch; ++b) pieces[s.seq0 + b] += 2;
+        for (const Segment& s : priv) pieces[s.seq0] += 1;
+        for (Segment& s : priv) s.whole_seq = pieces[s.seq0] == 1;
+    }
+
     // ---- workgroup shares: both kinds run in one launch and should finish together.  A workgroup of
     // the shared kind keeps fewer bytes in flight than one of the private kind and so gets a smaller
     // slice of a saturated memory system: its tokens are weighted by shared_cost_pct / 100.  Every
@@ -403,7 +412,8 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
             } else {  // its tail, from a block boundary
                 const int keep = (int)((s.n_tokens - want + kPrivateBlockTokens - 1) / kPrivateBlockTokens * kPrivateBlockTokens);
                 if (keep < s.n_tokens) {
-                    pool.push_back({s.seq0, s.n_branch, s.page0 + keep / 16, s.n_tokens - keep, s.kind, s.ends_seq});
+                    pool.push_back({s.seq0, s.n_branch, s.page0 + keep / 16, s.n_tokens - keep, s.kind, s.ends_seq, 0});
+                    s.whole_seq = 0;
                     cost_total -= s.n_tokens - keep + (s.ends_seq ? cost_priv.merge : 0);
                     s.n_tokens = keep;
                     s.ends_seq = 0;
