@@ -267,6 +267,14 @@ TAPER_API int taper_step_latency_probe(taper_ctx *ctx, const taper_plan *plan, i
  */
 TAPER_API int taper_kernel_times(taper_ctx *ctx, const taper_plan *plan, const void *q, const void *kv_pages, void *out,
                        int warmup, int iters, void *hip_stream, double us[2] /* host */);
+/* The same with launch i running on layer i mod n_layers (its q, pool and out): with enough
+ * distinct pools no launch finds KV of an earlier one in the 256 MB Infinity Cache, which
+ * repeated launches over one small pool do. */
+TAPER_API int taper_kernel_times_layers(taper_ctx *ctx, const taper_plan *plan, int n_layers,
+                              const void *const *q_per_layer /* host array of device ptrs */,
+                              const void *const *kv_per_layer /* host array of device ptrs */,
+                              void *const *out_per_layer /* host array of device ptrs */, int warmup, int iters,
+                              void *hip_stream, double us[2] /* host */);
 
 /*
  * KV append: the step before attention in a decode loop.  The token a sequence

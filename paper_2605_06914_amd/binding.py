@@ -21,7 +21,7 @@ TAPER_OK, TAPER_EINVAL, TAPER_EBLOCK, TAPER_EGROUP, TAPER_ELEN, TAPER_EHIP, TAPE
 EXPORTED = [
     "taper_create", "taper_destroy", "taper_plan_build", "taper_plan_free", "taper_plan_export",
     "taper_plan_resolve_slots_host", "taper_plan_resolve_slots", "taper_decode_step_attention",
-    "taper_decode_step_attention_simple", "taper_step_latency_probe", "taper_kernel_times",
+    "taper_decode_step_attention_simple", "taper_step_latency_probe", "taper_kernel_times", "taper_kernel_times_layers",
     "taper_strerror", "taper_last_error",
     "taper_plan_build_segments", "taper_append_slots", "taper_kv_append", "taper_branch_blocks",
     "taper_predictor_fit", "taper_predictor_eval", "taper_predictor_mape", "taper_window_create",
@@ -134,6 +134,8 @@ def load_library() -> ctypes.CDLL:
     lib.taper_step_latency_probe.argtypes = [vp, vp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                              ci, ci, vp, ctypes.POINTER(taper_probe_result)]
     lib.taper_kernel_times.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.taper_kernel_times_layers.argtypes = [vp, vp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, ci,
+                                              vp, ctypes.POINTER(ctypes.c_double)]
     dp, f64 = ctypes.POINTER(ctypes.c_double), ctypes.c_double
     pp = ctypes.POINTER(taper_predictor)
     lib.taper_predictor_fit.argtypes = [i64, vp, vp, vp, pp, dp]
@@ -328,6 +330,17 @@ class Context:
         us = (ctypes.c_double * 2)()
         _check(load_library().taper_kernel_times(self._h, plan._h, _ptr(q), _ptr(kv_pages), _ptr(out), warmup, iters,
                                                  _stream(stream), us))
+        return dict(decode_us=us[0], decode_us_min=us[1])
+
+    def kernel_times_layers(self, plan: Plan, q_layers: Sequence, kv_layers: Sequence, out_layers: Sequence,
+                            warmup: int = 5, iters: int = 20, stream=None):
+        """Launch i runs on layer i mod len(layers): distinct pools, so no launch reuses cached KV of an earlier one."""
+        n = len(q_layers)
+        assert len(kv_layers) == n and len(out_layers) == n
+        mk = lambda ts: (ctypes.c_void_p * n)(*[_ptr(t) for t in ts])
+        us = (ctypes.c_double * 2)()
+        _check(load_library().taper_kernel_times_layers(self._h, plan._h, n, mk(q_layers), mk(kv_layers), mk(out_layers),
+                                                        warmup, iters, _stream(stream), us))
         return dict(decode_us=us[0], decode_us_min=us[1])
 
 

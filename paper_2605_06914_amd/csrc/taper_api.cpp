@@ -518,16 +518,26 @@ int taper_step_latency_probe(taper_ctx* ctx, const taper_plan* plan, int n_layer
 
 int taper_kernel_times(taper_ctx* ctx, const taper_plan* plan, const void* q, const void* kv_pages, void* out,
                        int warmup, int iters, void* hip_stream, double us[2]) {
+    if (!q || !kv_pages || !out) return fail(TAPER_EINVAL, "bad argument");
+    return taper_kernel_times_layers(ctx, plan, 1, &q, &kv_pages, &out, warmup, iters, hip_stream, us);
+}
+
+int taper_kernel_times_layers(taper_ctx* ctx, const taper_plan* plan, int n_layers, const void* const* q_per_layer,
+                              const void* const* kv_per_layer, void* const* out_per_layer, int warmup, int iters,
+                              void* hip_stream, double us[2]) {
     int st = check_step(ctx, plan);
     if (st != TAPER_OK) return st;
-    if (!q || !kv_pages || !out || !us || iters < 1 || warmup < 0) return fail(TAPER_EINVAL, "bad argument");
+    if (!q_per_layer || !kv_per_layer || !out_per_layer || !us || n_layers < 1 || iters < 1 || warmup < 0)
+        return fail(TAPER_EINVAL, "bad argument");
+    for (int l = 0; l < n_layers; ++l)
+        if (!q_per_layer[l] || !kv_per_layer[l] || !out_per_layer[l]) return fail(TAPER_EINVAL, "null layer pointer");
     hipStream_t s = (hipStream_t)hip_stream;
-    const taper::StepArgs a = make_args(ctx, plan, q, kv_pages, out, nullptr);
     std::vector<hipEvent_t> ev(2 * (size_t)iters, nullptr);
     for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
     int rc = TAPER_OK;
     for (int i = 0; i < warmup + iters && rc == TAPER_OK; ++i) {
-        const int k = i - warmup;
+        const int k = i - warmup, l = i % n_layers;
+        const taper::StepArgs a = make_args(ctx, plan, q_per_layer[l], kv_per_layer[l], out_per_layer[l], nullptr);
         hipError_t e = hipSuccess;
         if (k >= 0) e = hipEventRecord(ev[2 * k], s);
         if (e == hipSuccess) e = taper::launch_decode(a, s);

@@ -350,6 +350,8 @@ def test_step_latency_probe_runs(ctx_qwen):
         assert_parity(f32_from_bf16_bits(bits_from_torch(o)).astype(np.float64), ref, "probe layer")
     kt = ctx_qwen.kernel_times(plan, q, kv, outs[0], warmup=1, iters=3)
     assert kt["decode_us"] >= kt["decode_us_min"] > 0
+    kt = ctx_qwen.kernel_times_layers(plan, [q] * 3, [kv] * 3, outs, warmup=1, iters=4)
+    assert kt["decode_us"] >= kt["decode_us_min"] > 0
     plan.free()
 
 
