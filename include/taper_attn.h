@@ -131,7 +131,8 @@ typedef struct {
 } taper_plan_view;
 
 typedef struct {
-    int32_t target_workgroups; /* 0 = default; workgroup shares the KV stream is cut into */
+    int32_t target_workgroups; /* workgroups the KV stream is cut for; 0 = default: two per compute unit
+                                  of the context's device (512 on MI355X, and on a host-only context) */
     int32_t share_prefix;      /* 1 = default: read each request's prefix once for all its
                                   branches; 0 = every branch streams the prefix by itself  */
     int32_t max_branches_per_item; /* 0 = default (8 row tiles: 16 branches at 8 query heads per KV

@@ -54,6 +54,7 @@ struct taper_ctx {
     int64_t ws_rows = 0;
     int64_t ws_counters = 0;
     std::vector<PlanBuffers> free_buffers;
+    int default_workgroups = 0;  // two resident workgroups per compute unit of the device (0: the builder's own default)
 };
 
 struct taper_plan {
@@ -279,6 +280,9 @@ int taper_create(const taper_attn_config* cfg, taper_ctx** out_ctx) {
             delete ctx;
             return fail_hip(e, "hipSetDevice");
         }
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device) == hipSuccess && cus > 0)
+            ctx->default_workgroups = 2 * cus;  // the decode kernel keeps two workgroups resident per compute unit
     }
     *out_ctx = ctx;
     return TAPER_OK;
@@ -311,8 +315,13 @@ int taper_plan_build_segments(taper_ctx* ctx, int n_seqs, const int32_t* block_t
     if (!plan) return fail(TAPER_ENOMEM, "host allocation failed");
     plan->ctx = ctx;
     std::string err;
+    taper_plan_options o;
+    std::memset(&o, 0, sizeof o);
+    o.share_prefix = 1;
+    if (opts) o = *opts;
+    if (o.target_workgroups <= 0) o.target_workgroups = ctx->default_workgroups;  // (0 on a host-only context: 512)
     int st = taper::build_host_plan_segments(ctx->cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len,
-                                             seg_start, seg_len, n_pool_pages, opts, &plan->host, &err);
+                                             seg_start, seg_len, n_pool_pages, &o, &plan->host, &err);
     if (st != TAPER_OK) {
         delete plan;
         return fail(st, err);
