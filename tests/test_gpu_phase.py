@@ -145,3 +145,49 @@ def test_decode_loop_append_then_attend(ctx_qwen):
         ref, _ = oracle.attention_segments(64, 8, 128, 16, QWEN.scale, q, kv_host, bt, seg.prefix_len, seg.seg_start, seg_len)
         assert_parity(f32_from_bf16_bits(bits_from_torch(out)).astype(np.float64), ref, f"decode loop step {step}")
     assert pages_opened >= 3
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_batches_and_options(ctx_qwen, seed):
+    """Random mixes of serial requests, parallel phases (1-20 branches, empty suffixes included) and reduce
+    sequences, under random plan options: same parity bar everywhere."""
+    import torch
+
+    rng = np.random.default_rng(1000 + seed)
+    reqs = []
+    for _ in range(int(rng.integers(3, 30))):
+        kind = rng.integers(0, 4)
+        if kind == 0:      # short serial
+            reqs.append((int(rng.integers(1, 400)), [0]))
+        elif kind == 1:    # long serial, context given as private tokens
+            reqs.append((0, [int(rng.integers(500, 5000))]))
+        else:              # parallel phase
+            width = int(rng.choice([2, 3, 4, 7, 8, 9, 16, 17, 20]))
+            reqs.append((int(rng.integers(1, 3000)), [int(x) for x in rng.integers(0, 300, size=width) * rng.integers(0, 2, size=width)]))
+    st = structure_custom(QWEN, reqs, seed=2000 + seed)
+    st = structure_custom(QWEN, reqs, seed=2000 + seed, n_pool_pages=st.n_pool_pages + 64)
+    b = fill_values_numpy(st)
+    n_groups = int(st.branch_group[-1]) + 1
+    keep = [g for g in range(n_groups) if rng.random() < 0.6]
+    seg = reduce_structure(st, z_len=[int(x) for x in rng.integers(0, 60, size=n_groups)], seed=seed, keep_parallel=keep)
+    opts = {}
+    if rng.random() < 0.5:
+        opts["target_workgroups"] = int(rng.choice([8, 64, 256, 1024, 4096]))
+    if rng.random() < 0.5:
+        opts["pool_pct"] = int(rng.choice([-1, 10, 50, 90]))
+    if rng.random() < 0.4:
+        opts["min_share_tokens"] = int(rng.choice([1, 64, 1000]))
+    if rng.random() < 0.3:
+        opts["solo_item_tokens"] = int(rng.choice([-1, 32, 4096]))
+    if rng.random() < 0.3:
+        opts["max_branches_per_item"] = int(rng.choice([2, 5, 24]))
+    if rng.random() < 0.2:
+        opts["share_prefix"] = 0
+    q = bf16_bits_from_f32(rng.standard_normal((seg.n_seqs, 64, 128), dtype=np.float32))
+    kv_dev = torch_bf16(b.kv)
+    plan, got, lse = run_segments_gpu(ctx_qwen, seg, q, kv_dev, **opts)
+    plan.free()
+    ref, ref_lse = oracle.attention_segments(64, 8, 128, 16, QWEN.scale, q, b.kv, seg.block_table, seg.prefix_len,
+                                             seg.seg_start, seg.seg_len)
+    assert_parity(got, ref, f"random batch {seed}: {seg.n_seqs} sequences, options {opts}")
+    assert np.max(np.abs(lse - ref_lse)) <= 2e-3
