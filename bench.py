@@ -436,12 +436,16 @@ def main():
     # q read and out written; the plan may list a prefix more than once (requests wider than one
     # workgroup's row tiles are cut into sub-groups), which is reported beside it, not counted
     dom_bytes = st.kv_bytes_unique + st.qo_bytes
-    achieved = dom_bytes / (kt["decode_us"] * 1e-6) / 1e9
+    # average launch duration: HIP events around whole steps of n_layers back-to-back launches on the launch
+    # stream (one launch per layer, each on its own pool), divided by n_layers.  Bracketing every single launch
+    # with its own pair of events (kernel_us_event_pairs) adds about 2 us of event handling per launch.
+    launch_us = probe.us_median / n_layers
+    achieved = dom_bytes / (launch_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                 "bytes_per_launch": dom_bytes, "kv_bytes_listed_by_plan": (tok_shared + tok_private) * sh.kv_bytes_per_token,
-                "avg_launch_us": round(kt["decode_us"], 2),
-                "kernel_us": {k: round(v, 2) for k, v in kt.items()},
+                "avg_launch_us": round(launch_us, 2), "min_launch_us": round(probe.us_min / n_layers, 2),
+                "kernel_us_event_pairs": {k: round(v, 2) for k, v in kt.items()},
                 "workgroups": (e["n_parts_shared"] + e["n_parts_private"]) * sh.n_kv_heads,
                 "pool_items": e["n_pool_items"]}
 
