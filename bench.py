@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="mixed", choices=["mixed", "irp_off", "long", "tiny", "sweep", "controller", "phase"])
+    ap.add_argument("--workload", default="mixed", choices=["mixed", "irp_off", "long", "tiny", "sweep", "controller", "phase", "decode_loop"])
     ap.add_argument("--layers", type=int, default=0, help="layers per step (0 = workload default)")
     ap.add_argument("--target-workgroups", type=int, default=0)
     ap.add_argument("--shared-cost-pct", type=int, default=0)
@@ -340,6 +340,79 @@ def run_phase(args):
     }
 
 
+def run_decode_loop(args):
+    """A multi-step decode loop on the mixed batch (config 3): every step appends each sequence's new K/V rows
+    in all layers (opening a page where a sequence's last one is full; pages come from a host free list, the
+    memory accounting of App. C), rebuilds the plan for the grown lengths and runs the attention of all layers.
+    Reports the time per decode step of the attention path (append + plan + attention), inputs resident in HBM."""
+    import torch
+
+    from paper_2605_06914_amd import Context, append_slots, branch_blocks
+    from taper_inputs import structure_config3
+
+    dev = torch.device("cuda:0")
+    st = structure_config3()
+    sh = st.shape
+    n_layers = args.layers or 64
+    n_steps = max(args.steps, 8)
+    S = st.n_seqs
+    spare = 4 * S  # pages the loop may open
+    n_pool_pages = st.n_pool_pages + spare
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(st.seed + 2000)
+    kvs = [torch.empty(n_pool_pages * sh.page_elems, device=dev, dtype=torch.bfloat16).normal_(generator=gen) for _ in range(n_layers)]
+    qs = [torch.randn((S, sh.n_q_heads, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16) for _ in range(n_layers)]
+    outs = [torch.zeros_like(q) for q in qs]
+    k_new = torch.randn((S, sh.n_kv_heads, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16)
+    v_new = torch.randn((S, sh.n_kv_heads, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16)
+    ctx = Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, device=0)
+    seg_start = np.arange(S + 1, dtype=np.int32)
+    P = sh.page_size
+
+    def run(n, timed):
+        bt = np.concatenate([st.block_table, np.full((S, 4), -1, np.int32)], axis=1)
+        suffix = st.suffix_len.copy()
+        free = list(range(st.n_pool_pages, n_pool_pages))
+        npp = -(-st.prefix_len // P)
+        opened = 0
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            full = np.flatnonzero(suffix % P == 0)
+            for s in full:  # this token opens a page: dM = +1 block for the sequence
+                bt[s, npp[s] + suffix[s] // P] = free.pop()
+            opened += len(full)
+            slots, _ = append_slots(bt, st.prefix_len, seg_start, suffix, P, n_pool_pages)
+            slots_dev = torch.from_numpy(slots).to(dev, non_blocking=True)
+            suffix += 1
+            plan = ctx.plan_build(bt, st.branch_group, st.prefix_len, suffix, n_pool_pages)
+            for l in range(n_layers):
+                ctx.kv_append(k_new, v_new, slots_dev, kvs[l], S)
+                ctx.decode_step_attention(plan, qs[l], kvs[l], outs[l])
+            plan.free()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        assert all(branch_blocks(int(x)) == -(-int(x) // P) for x in suffix[:4])
+        return dt / n, opened, suffix
+
+    run(max(2, args.warmup), False)
+    per_step, opened, suffix = run(n_steps, True)
+    assert bool(torch.isfinite(outs[0].float()).all())
+    ctx.close()
+    tokens_unique = int(st.unique_tokens + n_steps * S / 2)  # mean over the loop
+    gbps = tokens_unique * sh.kv_bytes_per_token * n_layers / per_step / 1e9
+    return {
+        "metric": "decode_step_attention_effective_kv_bandwidth", "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": n_steps, "warmup": args.warmup, "ms_per_step": round(per_step * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"decode loop on config3_mixed x {n_layers} layers: per step KV append of {S} rows per layer, "
+                               f"plan for the grown lengths, attention of all layers", "n_layers": n_layers, "n_seqs": S,
+                   "decode_steps": n_steps, "pages_opened": int(opened)},
+        "tokens_per_s": round(S / per_step, 1), "us_per_layer": round(per_step * 1e6 / n_layers, 2),
+        "frac_of_hbm_peak_whole_step": round(gbps / HBM_PEAK_GBPS, 4), "cpu_baseline": None,
+    }
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -360,6 +433,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}}))
+        return
+    if args.workload == "decode_loop":
+        print(json.dumps(run_decode_loop(args)))
         return
     if args.workload == "phase":
         print(json.dumps(run_phase(args)))
