@@ -458,8 +458,8 @@ def main():
     st = make_structure(args.workload)
     sh = st.shape
     # default depth: the 64-layer stack of the model the shape comes from; the long workload's pool is
-    # ~30 GB per layer, so it runs a shallower stack
-    n_layers = args.layers or {"mixed": 64, "irp_off": 64, "long": 4, "tiny": 64}[args.workload]
+    # ~30 GB per layer, so it runs a shallower stack (8 pools = 240 GB of the 288 GB)
+    n_layers = args.layers or {"mixed": 64, "irp_off": 64, "long": 8, "tiny": 64}[args.workload]
     pool_elems = st.n_pool_pages * sh.page_elems
     gen = torch.Generator(device=dev)
     gen.manual_seed(st.seed + 1000)
