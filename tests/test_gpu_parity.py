@@ -238,6 +238,19 @@ def test_many_short_sequences(ctx_qwen, kw):
     assert np.max(np.abs(lse - ref_lse)) <= 2e-3
 
 
+@pytest.mark.parametrize("gain", [0.02, 8.0, 40.0])
+def test_flat_and_peaked_softmax(ctx_qwen, gain):
+    """Scores scaled down (all weights nearly equal) and far up (one token takes almost all the weight, scores
+    of several thousand): the running maximum keeps every exponent in range."""
+    b = fill_values_numpy(structure_custom(QWEN, RAGGED, seed=112))
+    q = f32_from_bf16_bits(b.q) * np.float32(gain)
+    b = Batch(b.structure, bf16_bits_from_f32(q), b.kv)
+    ref, ref_lse = run_oracle(b)
+    got, lse, _ = run_gpu(ctx_qwen, b)
+    assert_parity(got, ref, f"q scaled by {gain}")
+    assert np.max(np.abs(lse - ref_lse) / np.maximum(1.0, np.abs(ref_lse))) <= 2e-3
+
+
 def test_sibling_independence(ctx_qwen):
     """Lemma 1: which siblings share the step must not change a branch's output
     (beyond summation order; the prefix partial is computed per row, so it is in
