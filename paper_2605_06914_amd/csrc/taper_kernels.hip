@@ -26,6 +26,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 #define DEV __device__ __forceinline__
 
@@ -129,6 +130,31 @@ DEV int opaque(int v) {
     asm volatile("" : "+v"(v));
     return v;
 }
+// V of the invalid tokens of a chunk's last 32-token block -> 0, so that whatever bits an
+// unwritten slot holds (NaN, Inf) meet their zero weight as 0 * 0.  A lane's values are tokens
+// 4*qd+i of the first page (va) and of the second (vb), two per dword.  The comparisons are made
+// again for every dword pair (from `opaque`) rather than kept: this runs once per chunk, in
+// code that has no register to spare.
+DEV unsigned keep_pair(unsigned w, int t) {  // both halves if t >= 2, the low one if t == 1, none below
+    const unsigned lo = __builtin_amdgcn_ubfe(w, 0, 16);  // (no 32-bit literal: those get hoisted into registers)
+    return t > 1 ? w : (t > 0 ? lo : 0u);
+}
+DEV bf16x4 keep_tail(bf16x4 v, int t) {  // tokens i < t of the four
+    u32x2 w = __builtin_bit_cast(u32x2, v);
+    w[0] = keep_pair(w[0], t);
+    w[1] = keep_pair(w[1], t - 2);
+    return __builtin_bit_cast(bf16x4, w);
+}
+template <int DT>
+DEV void zero_tail(bf16x4 (&va)[DT], bf16x4 (&vb)[DT], int qd, int n_valid) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+        const int t = opaque(n_valid - 4 * qd);
+        va[dt] = keep_tail(va[dt], t);
+        vb[dt] = keep_tail(vb[dt], t - 16);
+    }
+}
+
 DEV MetaRegs meta_load(const StepArgs& a, const taper_work_item& item, const int tid_) {
     const int tid = opaque(tid_);
     MetaRegs r;
@@ -318,7 +344,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
                 r.vb[dt] = stream_load((const bf16x4*)(vb + voff + dt * 64));
             }
         };
-        auto compute_block = [&](int b, const KVRegs<D>& r) {
+        auto compute_block = [&](int b, KVRegs<D>& r) {
             f32x4 sx = (f32x4)(0.f), sy = (f32x4)(0.f);
 #pragma unroll
             for (int j = 0; j < KS; ++j) {
@@ -328,6 +354,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
             const int nv = n_tok - 32 * b;
             if (nv < 32) mask_tail(sx, sy, qd, nv);
             const bf16x8 pf = softmax_block<DT>(sx, sy, c, m, l, O);
+            if (nv < 32) zero_tail(r.va, r.vb, qd, nv);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) O[dt] = mfma16(cat(r.va[dt], r.vb[dt]), pf, O[dt]);
         };
@@ -585,7 +612,12 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
                 }
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
-                    const bf16x8 vf = cat(*(const bf16x4*)(pa + voff + dt * 64), *(const bf16x4*)(pb + voff + dt * 64));
+                    bf16x4 va = *(const bf16x4*)(pa + voff + dt * 64), vb = *(const bf16x4*)(pb + voff + dt * 64);
+                    if (nv < 32) {
+                        va = keep_tail(va, nv - 4 * qd);
+                        vb = keep_tail(vb, nv - 4 * qd - 16);
+                    }
+                    const bf16x8 vf = cat(va, vb);
 #pragma unroll
                     for (int k = 0; k < NTW; ++k)
                         if (k < n_act) O[k][dt] = mfma16(vf, pf[k], O[k][dt]);

@@ -89,8 +89,8 @@ def test_wide_requests_tiny_shape(ctx_tiny, width):
     assert_parity(got, ref, f"tiny width={width}")
 
 
-def poison(b: Batch, val=1e30):
-    """+-val in every slot no sequence may read."""
+def poison(b: Batch, val=1e30, bits=None):
+    """+-val (or the two given bf16 bit patterns) in every slot no sequence may read."""
     st, sh = b.structure, b.structure.shape
     P = sh.page_size
     valid = np.zeros((st.n_pool_pages, P), bool)
@@ -106,6 +106,8 @@ def poison(b: Batch, val=1e30):
     d = np.arange(sh.head_dim)
     pos = bf16_bits_from_f32(np.array([val], np.float32))[0]
     neg = bf16_bits_from_f32(np.array([-val], np.float32))[0]
+    if bits is not None:
+        pos, neg = np.uint16(bits[0]), np.uint16(bits[1])
     pages, toks = np.nonzero(~valid)
     for page, tok in zip(pages, toks):
         for hk in range(sh.n_kv_heads):
@@ -121,6 +123,21 @@ def test_garbage_in_invalid_slots_changes_nothing(ctx_qwen):
     got, _, bits1 = run_gpu(ctx_qwen, b)
     ref, _ = run_oracle(b)
     assert_parity(got, ref, "poisoned")
+    assert np.array_equal(bits0, bits1)
+
+
+@pytest.mark.parametrize("bits", [(0x7FC0, 0xFFC0), (0x7F80, 0xFF80), (0x7FC0, 0x7F80)], ids=["nan", "inf", "nan_inf"])
+@pytest.mark.parametrize("share", [1, 0])
+def test_nan_and_inf_in_invalid_slots_change_nothing(ctx_qwen, bits, share):
+    """Unwritten slots of a half-filled page may hold any bits, NaN and Inf included (pages come
+    from an allocator, not zeroed): K there is masked after the scores, V there must not meet
+    its zero weight as 0 * NaN.  Both the shared-prefix and the per-sequence kernels' tails."""
+    reqs = [(37, [0]), (50, [0, 7, 16, 21]), (16, [1]), (133, [3, 70]), (1, [0]), (15, [17, 1]), (17, [15, 33])]
+    b = fill_values_numpy(structure_custom(QWEN, reqs, seed=105))
+    _, _, bits0 = run_gpu(ctx_qwen, b, share_prefix=share)
+    poison(b, bits=bits)
+    got, _, bits1 = run_gpu(ctx_qwen, b, share_prefix=share)
+    assert np.isfinite(got).all()
     assert np.array_equal(bits0, bits1)
 
 

@@ -69,6 +69,36 @@ def test_reduce_phase_attention(ctx_qwen, keep, opts):
     plan.free()
 
 
+def test_reduce_phase_ignores_non_finite_bits_in_unwritten_slots(ctx_qwen):
+    """A reduce sequence crosses the half-filled last page of every branch it absorbs: NaN / Inf
+    bits in those pages' unwritten slots (and in pages nobody lists) must leave the result as it is."""
+    from tests.layout_ref import PoolView
+
+    b = parallel_batch(QWEN, seed=41)
+    seg = reduce_structure(b.structure, z_len=[0, 9, 130, 1, 17, 64], seed=42, keep_parallel=(1, 5))
+    rng = np.random.Generator(np.random.PCG64(43))
+    q = bf16_bits_from_f32(rng.standard_normal((seg.n_seqs, 64, 128), dtype=np.float32))
+    plan, got0, _ = run_segments_gpu(ctx_qwen, seg, q, torch_bf16(b.kv))
+    plan.free()
+    ctx_len, _, slots = oracle.resolve_segments(16, seg.block_table, seg.prefix_len, seg.seg_start, seg.seg_len)
+    valid = np.zeros(seg.n_pool_pages * 16, bool)
+    valid[slots[slots >= 0]] = True
+    assert 0 < valid.sum() < valid.size
+    pv = PoolView(8, 128, 16)
+    kv = b.kv.copy()
+    flat = kv.reshape(-1)
+    d = np.arange(128)
+    for slot in np.nonzero(~valid)[0]:
+        page, tok = divmod(int(slot), 16)
+        for hk in range(8):
+            flat[pv.k_off(page, hk, tok, d)] = np.where(d % 3 == 0, 0x7FC0, np.where(d % 3 == 1, 0x7F80, 0xFF80)).astype(np.uint16)
+            flat[pv.v_off(page, hk, tok, d)] = np.where(d % 3 == 0, 0xFF80, np.where(d % 3 == 1, 0x7FC0, 0x7F80)).astype(np.uint16)
+    plan, got1, _ = run_segments_gpu(ctx_qwen, seg, q, torch_bf16(kv))
+    plan.free()
+    assert np.isfinite(got1).all()
+    assert np.array_equal(got0, got1)
+
+
 def test_kv_append_is_bit_exact(ctx_qwen):
     import torch
 
