@@ -135,12 +135,14 @@ typedef struct {
                                   of the context's device (512 on MI355X, and on a host-only context) */
     int32_t share_prefix;      /* 1 = default: read each request's prefix once for all its
                                   branches; 0 = every branch streams the prefix by itself  */
-    int32_t max_branches_per_item; /* 0 = default (8 row tiles: 16 branches at 8 query heads per KV
-                                      head); wider requests are cut into equal sub-groups of at
-                                      most this size; at most 12 row tiles                     */
+    int32_t max_branches_per_item; /* 0 = default (head_dim 128: 12 row tiles, 24 branches at 8
+                                      query heads per KV head; head_dim 64: 8 row tiles); wider
+                                      requests are cut into equal sub-groups of at most this
+                                      size; at most 12 row tiles                               */
     int32_t shared_cost_pct;   /* 0 = default (160 when no shared item is wider than 4 row tiles,
-                                  else 200): cost of a shared-prefix token relative to a private
-                                  one when cutting the work into equal shares                   */
+                                  200 up to 8, 140 above at head_dim 128): cost of a
+                                  shared-prefix token relative to a private one when cutting
+                                  the work into equal shares                                    */
     int32_t shared_item_cost;  /* 0 = default (800): fixed cost of a shared-prefix item, in private
                                   tokens' streaming time                                       */
     int32_t private_item_cost; /* 0 = default (128): fixed cost of a private item, same unit      */

@@ -700,11 +700,216 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
 }
 
 // ---------------------------------------------------------------------------
+// Shared-prefix kernel for requests wider than 8 row tiles (9 to 12: up to 24 branches at
+// 8 query heads per KV head), head_dim 128.  Three tiles per wave leave no registers for
+// staging sets, so KV goes from global memory straight into LDS: every wave-level 16-byte
+// load lands as 1 KiB at a wave-uniform LDS address, lane after lane, which is exactly one
+// quarter of a K tile or one (padded) quarter of a V tile.  Four 32-token buffers: one is
+// computed from while three are in flight.
+//
+// The compiler does not see which buffer an LDS read touches and would wait for every
+// outstanding load before each one, so the fragment reads are written out (with their own
+// wait), and the barrier is the bare instruction behind an explicit wait: "all but the
+// loads of the blocks after this one have landed, and my LDS reads are done".
+// ---------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+DEV unsigned lds_address(const void* p) { return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const char*)p; }
+// Two block-table entries through the scalar cache.  (The compiler reads the table with vector
+// loads once direct-to-LDS loads are in the loop, and a vector load's completion waits for
+// every load issued before it: the pipeline would drain at each one.)  The wait is part of
+// the statement: the compiler may copy the results right after it.
+DEV void page_ids_fetch(const int32_t* px, const int32_t* py, int& x, int& y) {
+    asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=&s"(x), "=&s"(y) : "s"(px), "s"(py));
+}
+template <int N>
+DEV void wait_loads_but() { asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(N)); }
+
+// K fragments of a 32-token block: four 16-byte reads per page, 1 KiB apart; PB = bytes from one page to the next
+template <int PB>
+DEV void lds_read_k(unsigned addr, bf16x8 (&kx)[4], bf16x8 (&ky)[4]) {
+    asm volatile(
+        "ds_read_b128 %0, %8\n\t"
+        "ds_read_b128 %1, %8 offset:1024\n\t"
+        "ds_read_b128 %2, %8 offset:2048\n\t"
+        "ds_read_b128 %3, %8 offset:3072\n\t"
+        "ds_read_b128 %4, %8 offset:%9\n\t"
+        "ds_read_b128 %5, %8 offset:%10\n\t"
+        "ds_read_b128 %6, %8 offset:%11\n\t"
+        "ds_read_b128 %7, %8 offset:%12\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(kx[0]), "=&v"(kx[1]), "=&v"(kx[2]), "=&v"(kx[3]), "=&v"(ky[0]), "=&v"(ky[1]), "=&v"(ky[2]), "=&v"(ky[3])
+        : "v"(addr), "n"(PB), "n"(PB + 1024), "n"(PB + 2048), "n"(PB + 3072));
+}
+// V fragments of four consecutive 16-dim groups (128 bytes apart), both pages
+template <int PB>
+DEV void lds_read_v(unsigned addr, bf16x4 (&va)[4], bf16x4 (&vb)[4]) {
+    asm volatile(
+        "ds_read_b64 %0, %8\n\t"
+        "ds_read_b64 %1, %8 offset:128\n\t"
+        "ds_read_b64 %2, %8 offset:256\n\t"
+        "ds_read_b64 %3, %8 offset:384\n\t"
+        "ds_read_b64 %4, %8 offset:%9\n\t"
+        "ds_read_b64 %5, %8 offset:%10\n\t"
+        "ds_read_b64 %6, %8 offset:%11\n\t"
+        "ds_read_b64 %7, %8 offset:%12\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(va[0]), "=&v"(va[1]), "=&v"(va[2]), "=&v"(va[3]), "=&v"(vb[0]), "=&v"(vb[1]), "=&v"(vb[2]), "=&v"(vb[3])
+        : "v"(addr), "n"(PB), "n"(PB + 128), "n"(PB + 256), "n"(PB + 384));
+}
+
+template <int D>
+DEV void shared_path_wide(const StepArgs& a, const int part, const int hk, SharedSmem<D>& sm) {
+    static_assert(D == 128, "a wave's 64 x 16 bytes must be one quarter of a tile");
+    constexpr int NTW = 3, KS = D / 32, DT = D / 16, TILE = 16 * D;
+    constexpr int QE = SharedSmem<D>::QE, VQ = SharedSmem<D>::VQ, PAGE_LDS = SharedSmem<D>::PAGE_LDS;
+    constexpr int BLK = 2 * PAGE_LDS;  // one 32-token buffer; sm.kv holds four
+    constexpr int PB = 2 * PAGE_LDS;   // bytes per page in LDS
+    __bf16* lds = sm.kv;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int Hkv = a.n_kv_heads, g = a.gqa;
+    const __bf16* __restrict__ kvb = (const __bf16*)a.kv;
+    const int64_t page_elems = 2LL * Hkv * TILE;
+    const float c = a.scale_log2e;
+
+    const int it0 = a.part_start[part], it1 = a.part_start[part + 1];
+    for (int it = it0; it < it1; ++it) {
+        const int tid = opaque(threadIdx.x);
+        const int lane = tid & 63;
+        const int n = lane & 15, qd = lane >> 4;
+        const int se = tid * 8;  // this thread's 8 elements of every tile it stages
+        const taper_work_item item = a.items[it];
+        const int32_t* __restrict__ row = a.bt + (int64_t)item.seq0 * a.bt_stride + item.page0;
+        const int n_tok = item.n_tokens;
+        const int n_pages = (n_tok + 15) >> 4;
+        const int n_blocks = (n_tok + 31) >> 5;
+        const int R = item.n_branch * g;
+        const int tiles = (R + 15) >> 4;
+        int n_act = (tiles - wave + 3) >> 2;
+        n_act = n_act < 0 ? 0 : (n_act > NTW ? NTW : n_act);
+        meta_store(sm.meta, meta_load(a, item, tid), item.n_branch, tid);
+
+        bf16x8 qf[NTW][KS];
+        float m[NTW], l[NTW];
+        f32x4 O[NTW][DT];
+#pragma unroll
+        for (int k = 0; k < NTW; ++k) {
+            const int r = 16 * (wave + 4 * k) + n;
+            const bool ok = k < n_act && r < R;
+            const int rr = ok ? r : 0;
+            const __bf16* qrow = (const __bf16*)a.q + ((int64_t)(item.seq0 + rr / g) * a.n_q_heads + hk * g + rr % g) * D;
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                bf16x8 v = *(const bf16x8*)(qrow + 8 * (4 * j + qd));
+                if (!ok) v = (bf16x8)(0);
+                qf[k][j] = v;
+            }
+            m[k] = -INFINITY;
+            l[k] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) O[k][dt] = (f32x4)(0.f);
+        }
+
+        // 4 loads of 16 bytes per thread and block: K and V quarter `wave` of both pages
+        int pid0, pid1;  // the pool pages of the block staged next (wave-uniform)
+        auto fetch_ids = [&](int b) {  // past the last page (an odd count's second page, a block that does not exist): the last page
+            const int i0 = 2 * b < n_pages ? 2 * b : n_pages - 1, i1 = 2 * b + 1 < n_pages ? 2 * b + 1 : n_pages - 1;
+            page_ids_fetch(row + i0, row + i1, pid0, pid1);
+        };
+        auto stage = [&](int b) {
+            __bf16* buf = lds + (b & 3) * BLK;
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg) {
+                const int64_t pid = pg ? pid1 : pid0;
+                const __bf16* kp = kvb + pid * page_elems + (int64_t)hk * TILE + se;
+                __builtin_amdgcn_global_load_lds((global_void_ptr)kp, (lds_void_ptr)(buf + pg * PAGE_LDS + wave * QE), 16, 0, 2);
+                __builtin_amdgcn_global_load_lds((global_void_ptr)(kp + (int64_t)Hkv * TILE),
+                                                 (lds_void_ptr)(buf + pg * PAGE_LDS + TILE + wave * VQ), 16, 0, 2);
+            }
+        };
+        auto compute = [&](int b) {
+            const int nv = n_tok - 32 * b;
+            const unsigned base = lds_address(lds + (b & 3) * BLK);
+            bf16x8 kx[KS], ky[KS];
+            lds_read_k<PB>(base + lane * 16, kx, ky);
+            bf16x8 pf[NTW];
+#pragma unroll
+            for (int k = 0; k < NTW; ++k) {
+                if (k < n_act) {
+                    f32x4 sx = (f32x4)(0.f), sy = (f32x4)(0.f);
+#pragma unroll
+                    for (int j = 0; j < KS; ++j) {
+                        sx = mfma16(kx[j], qf[k][j], sx);
+                        sy = mfma16(ky[j], qf[k][j], sy);
+                    }
+                    if (nv < 32) mask_tail(sx, sy, qd, nv);
+                    pf[k] = softmax_block<DT>(sx, sy, c, m[k], l[k], O[k]);
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < DT / 4; ++h) {
+                bf16x4 va[4], vb[4];
+                lds_read_v<PB>(base + 2 * (TILE + qd * VQ + n * 4) + h * 512, va, vb);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (nv < 32) {
+                        va[i] = keep_tail(va[i], nv - 4 * qd);
+                        vb[i] = keep_tail(vb[i], nv - 4 * qd - 16);
+                    }
+                    const bf16x8 vf = cat(va[i], vb[i]);
+#pragma unroll
+                    for (int k = 0; k < NTW; ++k)
+                        if (k < n_act) O[k][4 * h + i] = mfma16(vf, pf[k], O[k][4 * h + i]);
+                }
+            }
+        };
+
+        // (the previous item's LDS reads of these buffers ended before its closing barriers)
+        for (int b = 0; b < 3; ++b) {
+            fetch_ids(b);
+            if (b < n_blocks) stage(b);
+        }
+        fetch_ids(3);
+        for (int b = 0; b < n_blocks; ++b) {
+            const int after = n_blocks - 1 - b;  // blocks staged behind this one: 12, 8 or 4 loads may stay in flight
+            if (after >= 2) wait_loads_but<8>();
+            else if (after == 1) wait_loads_but<4>();
+            else wait_loads_but<0>();
+            __builtin_amdgcn_s_barrier();  // block b is in LDS for every wave; everyone is done with block b - 1
+            if (b + 3 < n_blocks) stage(b + 3);  // into the buffer block b - 1 was computed from
+            if (n_act > 0) compute(b);
+            fetch_ids(b + 4);  // for the next iteration's stage: its latency overlaps the wait for block b + 1
+        }
+
+#pragma unroll
+        for (int k = 0; k < NTW; ++k) {
+            if (k < n_act) {
+                const float lt = sum_lane_groups(l[k]);
+                const int r = 16 * (wave + 4 * k) + n;
+                if (r < R) {
+                    const int64_t slot = (int64_t)item.part_base + (int64_t)hk * R + r;
+                    if (qd == 0) coherent_store2((float*)(a.ws_ml + slot), m[k], lt);
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) coherent_store4(a.ws_o + slot * D + 16 * dt + 4 * qd, O[k][dt]);
+                }
+            }
+        }
+        stores_done();
+        __syncthreads();
+        if (tid < item.n_branch) sm.last[tid] = arrive_last(a, item.seq0 + tid, hk, sm.meta.ms[tid + 1] - sm.meta.ms[tid]);
+        __syncthreads();
+        for (int b = wave; b < item.n_branch; b += 4)
+            if (sm.last[b]) merge_rows<D, D / 32, 8>(a, sm.meta, item.seq0 + b, hk, sm.meta.ms[b], sm.meta.ms[b + 1], lane, 64);
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
 // One launch per layer: workgroup (share, kv head).  Shares below n_parts_shared
 // stream shared prefixes, the others private tokens; both kinds run side by side.
 // ---------------------------------------------------------------------------
 template <int D, int NTW>
-__global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void decode_kernel(StepArgs a) {
+__global__ __launch_bounds__(256, (NTW <= 2 || D == 128 ? 2 : 1)) void decode_kernel(StepArgs a) {
     union Smem {
         SharedSmem<D> sh;
         PrivateSmem<D> pr;
@@ -718,7 +923,10 @@ __global__ __launch_bounds__(256, (NTW <= 2 ? 2 : 1)) void decode_kernel(StepArg
 #endif
     int it0 = 0, it1 = 0;  // private items of this workgroup's share
     if (part < a.n_parts_shared) {
-        shared_path<D, NTW>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
+        if constexpr (NTW == 3 && D == 128)
+            shared_path_wide<D>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
+        else
+            shared_path<D, NTW>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
         __syncthreads();
     } else {
         it0 = a.part_start[part];

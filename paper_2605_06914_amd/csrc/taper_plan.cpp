@@ -221,10 +221,12 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
     const int g = cfg.n_q_heads / cfg.n_kv_heads;
     int target_wgs = opts && opts->target_workgroups > 0 ? opts->target_workgroups : 512;
     const bool share_prefix = opts ? opts->share_prefix != 0 : true;
-    // A shared item of up to 8 row tiles runs with two workgroups per compute unit; up to 12 tiles
-    // are possible, with one.  64: per-branch flags of the shared kernel.
+    // A shared item holds up to 12 row tiles.  At head_dim 128 the kernel for 9 to 12 tiles loads
+    // straight into LDS and still runs two workgroups per compute unit; at 64 it stages through
+    // registers and runs one, so requests are cut at 8 tiles unless asked otherwise.
+    // 64: per-branch flags of the shared kernel.
     const int hard_cap = std::min(64, std::max(2, kMaxRowTilesPerItem * 16 / g));
-    int cap_branches = std::min(hard_cap, std::max(2, 8 * 16 / g));
+    int cap_branches = std::min(hard_cap, std::max(2, (cfg.head_dim == 128 ? kMaxRowTilesPerItem : 8) * 16 / g));
     if (opts && opts->max_branches_per_item > 0) cap_branches = std::max(1, std::min(hard_cap, opts->max_branches_per_item));
 
     HostPlan& p = *out;
@@ -373,9 +375,10 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
     // slice of a saturated memory system: its tokens are weighted by shared_cost_pct / 100.  Every
     // item also has a fixed cost (a shared item's is large: rows of several branches to store, and
     // the merges of all branches it completes).
-    int widest = 0;  // row tiles of the widest shared item: up to 4, the kernel stages with three register sets
+    int widest = 0;  // row tiles of the widest shared item: up to 4, the kernel stages with three register sets,
+                     // up to 8 with two, above that straight into LDS (measured weights for each)
     for (const Segment& s : shared) widest = std::max(widest, (s.n_branch * g + 15) / 16);
-    const Cost cost_shared = {opts && opts->shared_cost_pct > 0 ? opts->shared_cost_pct : (widest <= 4 ? 160 : 200),
+    const Cost cost_shared = {opts && opts->shared_cost_pct > 0 ? opts->shared_cost_pct : (widest <= 4 ? 160 : (widest <= 8 || cfg.head_dim != 128) ? 200 : 140),
                               opts && opts->shared_item_cost > 0 ? opts->shared_item_cost : 800};
     const Cost cost_priv = {100, opts && opts->private_item_cost > 0 ? opts->private_item_cost : 128,
                             opts && opts->private_merge_cost != 0 ? std::max(0, opts->private_merge_cost)

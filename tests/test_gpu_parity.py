@@ -170,6 +170,27 @@ def test_plan_options_do_not_change_the_result(ctx_qwen, kw):
     assert np.max(np.abs(lse - ref_lse)) <= 2e-3
 
 
+@pytest.mark.parametrize("width", [17, 20, 24])
+def test_wide_requests_in_one_pass(ctx_qwen, width):
+    """Requests of 9 to 12 row tiles served by one item per prefix chunk (the kernel variant that loads
+    straight into LDS, four 32-token buffers): prefix lengths around every block and page boundary,
+    so one to many blocks, odd page counts and ragged tails; narrower requests ride in the same launch."""
+    rng = np.random.default_rng(400 + width)
+    reqs = [(pl, [int(x) for x in rng.integers(0, 40, size=width)]) for pl in (1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 95, 96, 97, 129, 1000)]
+    reqs += [(77, [0]), (300, [5, 0, 9]), (2500, [int(x) for x in rng.integers(0, 90, size=width)]), (500, [1] * 9)]
+    b = fill_values_numpy(structure_custom(QWEN, reqs, seed=400 + width))
+    ref, ref_lse = run_oracle(b)
+    got, lse, bits0 = run_gpu(ctx_qwen, b, max_branches_per_item=24)
+    assert_parity(got, ref, f"wide {width}")
+    assert np.max(np.abs(lse - ref_lse)) <= 2e-3
+    poison(b, bits=(0x7FC0, 0xFF80))
+    _, _, bits1 = run_gpu(ctx_qwen, b, max_branches_per_item=24)
+    assert np.array_equal(bits0, bits1)
+    _, _, bits2 = run_gpu(ctx_qwen, b, max_branches_per_item=24, target_workgroups=8)
+    got2 = f32_from_bf16_bits(bits2).astype(np.float64)
+    assert_parity(got2, ref, f"wide {width}, 8 workgroups")
+
+
 def test_same_plan_replayed(ctx_qwen):
     """The arrival counters and the pool's claim counter reset themselves inside the
     kernel: replaying one plan must give the same bits every time."""

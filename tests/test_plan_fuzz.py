@@ -73,8 +73,8 @@ def test_random_plans_are_exact_covers_with_in_bounds_indices(seed):
     bt = np.asarray(seg.block_table)
     where = [{int(v): i for i, v in enumerate(slots[s, : ctx_len[s]])} for s in range(seg.n_seqs)]
     cover = [np.zeros(int(c), np.int32) for c in ctx_len]
-    # default: 8 tiles of 16 rows per item; an option may raise that to 12 tiles at most
-    cap = min(opts.get("max_branches_per_item", 0) or 8 * 16 // g, 12 * 16 // g)
+    # default: 12 tiles of 16 rows per item at head_dim 128, 8 at 64; an option may set up to 12
+    cap = min(opts.get("max_branches_per_item", 0) or (12 if shape.head_dim == 128 else 8) * 16 // g, 12 * 16 // g)
     for it in items:
         seq0, nb, page0, ntok, kind, base = (int(it[F[k]]) for k in ("seq0", "n_branch", "page0", "n_tokens", "kind", "part_base"))
         assert 1 <= nb <= cap and ntok >= 1
