@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times: scales the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--sweep-pools", type=int, default=16, help="distinct KV pools the 64 layers of the sweep cycle through")
+    ap.add_argument("--sweep-k", default="0,2,4,8,16", help="widths of the admission sweep to run (k = 0 is always run: the base)")
     return ap.parse_args()
 
 
@@ -63,9 +64,10 @@ def run_sweep(args):
 
     dev = torch.device("cuda:0")
     n_layers = args.layers or 64
-    sts = {k: structure_config5(k) for k in (0, 2, 4, 8, 16)}
+    ks = sorted({0} | {int(x) for x in args.sweep_k.split(",")})
+    sts = {k: structure_config5(k) for k in ks}
     sh = sts[0].shape
-    n_pool_pages = sts[16].n_pool_pages
+    n_pool_pages = sts[ks[-1]].n_pool_pages
     assert all(st.n_pool_pages == n_pool_pages for st in sts.values())
     gen = torch.Generator(device=dev)
     gen.manual_seed(sts[0].seed + 1000)
@@ -78,7 +80,7 @@ def run_sweep(args):
             n = min(chunk, pool_elems - o)
             kv[o : o + n] = torch.randn(n, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
         pools.append(kv)
-    s_max = sts[16].n_seqs
+    s_max = sts[ks[-1]].n_seqs
     qs = [torch.randn((s_max, sh.n_q_heads, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16)
           for _ in range(n_layers)]
     outs = [torch.zeros((s_max, sh.n_q_heads, sh.head_dim), device=dev, dtype=torch.bfloat16) for _ in range(n_layers)]
@@ -450,7 +452,7 @@ def main():
             "metric": "decode_step_attention_effective_kv_bandwidth", "value": top["gbps_unique"], "unit": "GB/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": top["ms_per_step"],
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": f"config5 admission sweep x {n_layers} layers, value quoted at k=16 "
+            "config": {"workload": f"config5 admission sweep x {n_layers} layers, value quoted at k={top['k']} "
                                    f"({args.sweep_pools} distinct KV pools cycled over the layers)",
                        "n_layers": n_layers},
             "step_latency_vs_admitted_branches": rows}))
