@@ -482,3 +482,34 @@ def test_config5_sweep_point_sampled(ctx_qwen, k):
     ref, _ = run_oracle(sub)
     got = f32_from_bf16_bits(bits_from_torch(out[torch.from_numpy(rows).to(out.device)])).astype(np.float64)
     assert_parity(got, ref, f"config5 k={k} sampled")
+
+
+def test_config5_k16_every_output_two_ways(ctx_qwen):
+    """k = 16 at full size through both routes for 17-branch requests: one item of 9 row tiles per prefix
+    chunk (loads straight into LDS) and two sub-groups of 9 + 8 branches (register staging).  Every
+    output of the step is compared, not a sample; the one-pass route is replayed and must repeat its bits
+    (its barriers and waits are hand-placed: a race would show as a changing bit)."""
+    import torch
+
+    from taper_inputs import structure_config5
+    from tests.gpu_util import device_random_batch
+
+    st = structure_config5(16)
+    q, kv = device_random_batch(st)
+    outs = []
+    for cap in (24, 24, 24, 24, 16):
+        plan = ctx_qwen.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages,
+                                   max_branches_per_item=cap)
+        e = plan.export()
+        F = {n: i for i, n in enumerate(e["item_fields"])}
+        assert int(e["items"][:, F["n_branch"]].max()) == (17 if cap == 24 else 9)
+        out = torch.full_like(q, float("nan"))
+        ctx_qwen.decode_step_attention(plan, q, kv, out)
+        torch.cuda.synchronize()
+        plan.free()
+        outs.append(out)
+    for o in outs[1:4]:
+        assert torch.equal(outs[0].view(torch.int16), o.view(torch.int16))
+    a, b = outs[0].float(), outs[4].float()
+    assert bool(torch.isfinite(a).all()) and bool(torch.isfinite(b).all())
+    assert float((a - b).abs().max()) <= 2e-2 and float((a - b).abs().mean()) <= 2e-3
