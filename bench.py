@@ -36,6 +36,7 @@ def parse():
     ap.add_argument("--shared-cost-pct", type=int, default=0)
     ap.add_argument("--no-share", action="store_true", help="every branch streams its prefix itself (for comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-read-ceiling", action="store_true", help="skip the plain streaming-read measurement")
     ap.add_argument("--kernel-iters", type=int, default=50)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times: scales the FETCH_SIZE / WRITE_SIZE counters")
@@ -536,6 +537,21 @@ def main():
             roofline["traffic"] = t["fetch_bytes"] + t["write_bytes"]
             roofline["traffic_detail"] = {"fetch_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
                                           "source": "profiles/decode_kernel_%s.md" % args.workload}
+
+    # ---- what a plain streaming read reaches on this machine (context for `frac`, whose peak stays the
+    # published 8 TB/s): the same byte count and launch shape as the kernel, every launch on other bytes of an
+    # 8 GiB buffer (beyond the 256 MB Infinity Cache), and the whole buffer in one launch
+    if not args.no_read_ceiling:
+        buf = torch.zeros(8 << 30, dtype=torch.uint8, device=dev)
+        unit = 512 * 4096
+        launch_bytes = max(unit, min(8 << 30, dom_bytes // unit * unit))
+        r_launch = ctx.stream_read_probe(buf, launch_bytes, n_workgroups=512, warmup=4, iters=48)
+        r_whole = ctx.stream_read_probe(buf, 8 << 30, n_workgroups=512, warmup=1, iters=6)
+        del buf
+        roofline["plain_read"] = {"same_bytes_and_grid_gbps": round(r_launch["gbps"], 1),
+                                  "same_bytes_and_grid_us": round(r_launch["us"], 2), "bytes": launch_bytes,
+                                  "whole_8gib_gbps": round(r_whole["gbps"], 1), "workgroups": 512,
+                                  "kernel_over_plain_read": round(achieved / r_launch["gbps"], 4)}
 
     # ---- CPU oracle on a bounded sample of the same workload (rank 0, N=1)
     cpu = None

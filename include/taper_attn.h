@@ -280,6 +280,21 @@ TAPER_API int taper_kernel_times_layers(taper_ctx *ctx, const taper_plan *plan, 
                               void *hip_stream, double us[2] /* host */);
 
 /*
+ * Measurement aid, not a step of the path: a plain streaming read of device memory (16-byte
+ * nontemporal loads, `n_workgroups` workgroups of 256 threads, each reading a contiguous
+ * slice), timed with HIP events on `hip_stream` (synchronises).  Launch i reads the
+ * `pass_bytes` bytes at offset (i mod floor(buf_bytes / pass_bytes)) * pass_bytes of `buf`, so
+ * that with a buffer of several passes no launch finds an earlier one's bytes in the 256 MB
+ * Infinity Cache.  What it reaches for a kernel's own byte count and launch shape is the rate
+ * the machine leaves for that kernel; the published HBM peak stays the roofline's `peak`.
+ * pass_bytes: a positive multiple of n_workgroups * 4096, at most buf_bytes; buf 16-byte
+ * aligned.  us[0] = mean, us[1] = minimum microseconds per launch over `iters` after `warmup`.
+ * Allocates and frees a few bytes of device memory (the sink that keeps the loads alive).
+ */
+TAPER_API int taper_stream_read_probe(taper_ctx *ctx, const void *buf /* device */, int64_t buf_bytes, int64_t pass_bytes,
+                            int n_workgroups, int warmup, int iters, void *hip_stream, double us[2] /* host */);
+
+/*
  * KV append: the step before attention in a decode loop.  The token a sequence
  * generated in the previous step becomes part of its context: its key and value
  * rows are written into the sequence's last private segment, right after that

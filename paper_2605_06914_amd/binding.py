@@ -26,6 +26,7 @@ EXPORTED = [
     "taper_plan_build_segments", "taper_append_slots", "taper_kv_append", "taper_branch_blocks",
     "taper_predictor_fit", "taper_predictor_eval", "taper_predictor_mape", "taper_window_create",
     "taper_window_destroy", "taper_window_push", "taper_window_size", "taper_window_fit", "taper_admit_step",
+    "taper_stream_read_probe",
 ]
 
 
@@ -136,6 +137,7 @@ def load_library() -> ctypes.CDLL:
     lib.taper_kernel_times.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
     lib.taper_kernel_times_layers.argtypes = [vp, vp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), ci, ci,
                                               vp, ctypes.POINTER(ctypes.c_double)]
+    lib.taper_stream_read_probe.argtypes = [vp, vp, i64, i64, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
     dp, f64 = ctypes.POINTER(ctypes.c_double), ctypes.c_double
     pp = ctypes.POINTER(taper_predictor)
     lib.taper_predictor_fit.argtypes = [i64, vp, vp, vp, pp, dp]
@@ -342,6 +344,15 @@ class Context:
         _check(load_library().taper_kernel_times_layers(self._h, plan._h, n, mk(q_layers), mk(kv_layers), mk(out_layers),
                                                         warmup, iters, _stream(stream), us))
         return dict(decode_us=us[0], decode_us_min=us[1])
+
+    def stream_read_probe(self, buf, pass_bytes: int, n_workgroups: int = 512, warmup: int = 2, iters: int = 8, stream=None):
+        """Plain streaming read of `pass_bytes` per launch out of the device tensor `buf` (launches rotate over the
+        tensor).  Returns dict(us, us_min, gbps)."""
+        nbytes = buf.numel() * buf.element_size()
+        us = (ctypes.c_double * 2)()
+        _check(load_library().taper_stream_read_probe(self._h, _ptr(buf), nbytes, pass_bytes, n_workgroups, warmup, iters,
+                                                      _stream(stream), us))
+        return dict(us=us[0], us_min=us[1], gbps=pass_bytes / us[0] / 1e3)
 
 
 # ----------------------------------------------------------------------------- controller side (host only)

@@ -574,4 +574,54 @@ int taper_kernel_times_layers(taper_ctx* ctx, const taper_plan* plan, int n_laye
     return TAPER_OK;
 }
 
+int taper_stream_read_probe(taper_ctx* ctx, const void* buf, int64_t buf_bytes, int64_t pass_bytes, int n_workgroups,
+                            int warmup, int iters, void* hip_stream, double us[2]) {
+    if (!ctx || !buf || !us) return fail(TAPER_EINVAL, "null argument");
+    if (ctx->host_only) return fail(TAPER_EHIP, "context was created without a device");
+    if (n_workgroups < 1 || n_workgroups > 65536 || iters < 1 || warmup < 0) return fail(TAPER_EINVAL, "bad argument");
+    const int64_t unit = (int64_t)n_workgroups * 4096;
+    if (pass_bytes < unit || pass_bytes % unit != 0 || buf_bytes < pass_bytes)
+        return fail(TAPER_EINVAL, "pass_bytes must be a positive multiple of n_workgroups * 4096 and fit the buffer");
+    if (((uintptr_t)buf & 15) != 0) return fail(TAPER_EINVAL, "buffer must be 16-byte aligned");
+    HIP_TRY(hipSetDevice(ctx->cfg.device));
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int64_t n_regions = buf_bytes / pass_bytes, pieces_per_wg = pass_bytes / unit;
+    unsigned* sink = nullptr;
+    HIP_TRY(hipMalloc((void**)&sink, 256));
+    std::vector<hipEvent_t> ev(2 * (size_t)iters, nullptr);
+    int rc = TAPER_OK;
+    for (auto& e : ev)
+        if (rc == TAPER_OK && hipEventCreate(&e) != hipSuccess) rc = fail(TAPER_EHIP, "hipEventCreate");
+    for (int i = 0; i < warmup + iters && rc == TAPER_OK; ++i) {
+        const int k = i - warmup;
+        const char* base = (const char*)buf + (i % n_regions) * pass_bytes;
+        hipError_t e = hipSuccess;
+        if (k >= 0) e = hipEventRecord(ev[2 * k], s);
+        if (e == hipSuccess) e = taper::launch_stream_read(base, pieces_per_wg, n_workgroups, sink, s);
+        if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[2 * k + 1], s);
+        if (e != hipSuccess) rc = fail_hip(e, "read probe enqueue");
+    }
+    hipError_t es = hipStreamSynchronize(s);
+    if (rc == TAPER_OK && es != hipSuccess) rc = fail_hip(es, "hipStreamSynchronize");
+    double sum = 0, mn = 1e300;
+    if (rc == TAPER_OK) {
+        for (int k = 0; k < iters; ++k) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, ev[2 * k], ev[2 * k + 1]) != hipSuccess) {
+                rc = fail(TAPER_EHIP, "hipEventElapsedTime");
+                break;
+            }
+            sum += ms * 1000.0;
+            mn = std::min(mn, ms * 1000.0);
+        }
+    }
+    for (auto& e : ev)
+        if (e) (void)hipEventDestroy(e);
+    (void)hipFree(sink);
+    if (rc != TAPER_OK) return rc;
+    us[0] = sum / iters;
+    us[1] = mn;
+    return TAPER_OK;
+}
+
 }  // extern "C"

@@ -41,6 +41,7 @@ struct StepArgs {
 hipError_t launch_decode(const StepArgs& a, hipStream_t s);
 hipError_t launch_kv_append(const void* k_new, const void* v_new, const int64_t* slot, void* kv, int n_seqs, int n_kv_heads,
                             int head_dim, hipStream_t s);
+hipError_t launch_stream_read(const void* base, int64_t pieces_per_wg, int n_workgroups, unsigned* sink, hipStream_t s);
 hipError_t launch_resolve_slots(const StepArgs& a, int64_t* slots, int64_t stride, hipStream_t s);
 
 }  // namespace taper

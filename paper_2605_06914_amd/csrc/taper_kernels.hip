@@ -997,6 +997,38 @@ hipError_t launch_kv_append(const void* k_new, const void* v_new, const int64_t*
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Measurement aid, not a step of the path: a plain streaming read.  Every workgroup reads a
+// contiguous slice in 4 KiB pieces, 16 bytes per lane, nontemporal, two pieces per wave in
+// flight; nothing is computed but an XOR that keeps the loads alive.  What this reaches on the
+// same bytes and launch shape is the rate the machine leaves for any read-bound kernel.
+// ---------------------------------------------------------------------------
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ base, int64_t pieces_per_wg, unsigned* sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const u32x4* mine = base + (int64_t)blockIdx.x * pieces_per_wg * 256;  // 256 x 16 B = one 4 KiB piece
+    u32x4 acc = {0, 0, 0, 0};
+    for (int64_t i = 2 * wave; i < pieces_per_wg; i += 8) {
+        u32x4 v[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int64_t piece = i + u < pieces_per_wg ? i + u : i;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[u][k] = __builtin_nontemporal_load(mine + piece * 256 + 64 * k + lane);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc ^= v[u][k];
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u && sink) sink[0] = 1;  // (practically never: the loads must not be dropped)
+}
+
+hipError_t launch_stream_read(const void* base, int64_t pieces_per_wg, int n_workgroups, unsigned* sink, hipStream_t s) {
+    hipLaunchKernelGGL(stream_read_kernel, dim3(n_workgroups), dim3(256), 0, s, (const u32x4*)base, pieces_per_wg, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_decode(const StepArgs& a, hipStream_t s) {
     const int n_parts = a.n_parts_shared + a.n_parts_private;
     if (n_parts == 0) return hipSuccess;
