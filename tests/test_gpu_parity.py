@@ -252,6 +252,32 @@ def test_other_head_shapes(hq, hkv, d):
         ctx.close()
 
 
+def test_head_dim_64_with_three_tiles_per_wave():
+    """head_dim 64 serves 9 to 12 row tiles per item only when asked to (the variant stages through registers
+    and runs one workgroup per compute unit): 40 branches x 4 query heads per KV head = 10 tiles."""
+    from paper_2605_06914_amd import Context
+
+    sh = AttnShape(32, 8, 64, 16)
+    rng = np.random.default_rng(64)
+    reqs = [(pl, [int(x) for x in rng.integers(0, 50, size=40)]) for pl in (1, 63, 64, 65, 200, 1500)] + [(90, [0]), (40, [3, 0, 5])]
+    b = fill_values_numpy(structure_custom(sh, reqs, seed=164))
+    ctx = Context(32, 8, 64, device=0)
+    try:
+        ref, ref_lse = run_oracle(b)
+        st = b.structure
+        plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages, max_branches_per_item=48)
+        e = plan.export()
+        plan.free()
+        assert int(e["items"][:, e["item_fields"].index("n_branch")].max()) == 40
+        got, lse, _ = run_gpu(ctx, b, max_branches_per_item=48)
+        assert_parity(got, ref, "D64, 10 row tiles")
+        assert np.max(np.abs(lse - ref_lse)) <= 2e-3
+        got, _, _ = run_gpu(ctx, b)  # default: cut into sub-groups of at most 8 tiles
+        assert_parity(got, ref, "D64, default cap")
+    finally:
+        ctx.close()
+
+
 @pytest.mark.parametrize("kw", [{}, dict(solo_item_tokens=-1), dict(solo_item_tokens=64), dict(target_workgroups=64)])
 def test_many_short_sequences(ctx_qwen, kw):
     """Batches of short serial requests: each sequence is one item whose result the kernel writes directly
