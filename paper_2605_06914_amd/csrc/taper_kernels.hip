@@ -610,17 +610,25 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
                         pf[k] = softmax_block<DT>(sx, sy, c, m[k], l[k], O[k]);
                     }
                 }
+                // (four V fragment pairs at a time, then one branch for the ragged tail: a branch per
+                // fragment would keep the compiler from issuing the LDS reads ahead of the matrix
+                // instructions; all eight pairs at once do not fit the registers of two tiles per wave)
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    bf16x4 va = *(const bf16x4*)(pa + voff + dt * 64), vb = *(const bf16x4*)(pb + voff + dt * 64);
-                    if (nv < 32) {
-                        va = keep_tail(va, nv - 4 * qd);
-                        vb = keep_tail(vb, nv - 4 * qd - 16);
+                for (int h = 0; h < DT / 4; ++h) {
+                    bf16x4 va[4], vb[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        va[i] = *(const bf16x4*)(pa + voff + (4 * h + i) * 64);
+                        vb[i] = *(const bf16x4*)(pb + voff + (4 * h + i) * 64);
                     }
-                    const bf16x8 vf = cat(va, vb);
+                    if (nv < 32) zero_tail(va, vb, qd, nv);
 #pragma unroll
-                    for (int k = 0; k < NTW; ++k)
-                        if (k < n_act) O[k][dt] = mfma16(vf, pf[k], O[k][dt]);
+                    for (int i = 0; i < 4; ++i) {
+                        const bf16x8 vf = cat(va[i], vb[i]);
+#pragma unroll
+                        for (int k = 0; k < NTW; ++k)
+                            if (k < n_act) O[k][4 * h + i] = mfma16(vf, pf[k], O[k][4 * h + i]);
+                    }
                 }
             }
         };
@@ -850,12 +858,9 @@ DEV void shared_path_wide(const StepArgs& a, const int part, const int hk, Share
             for (int h = 0; h < DT / 4; ++h) {
                 bf16x4 va[4], vb[4];
                 lds_read_v<PB>(base + 2 * (TILE + qd * VQ + n * 4) + h * 512, va, vb);
+                if (nv < 32) zero_tail(va, vb, qd, nv);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    if (nv < 32) {
-                        va[i] = keep_tail(va[i], nv - 4 * qd);
-                        vb[i] = keep_tail(vb[i], nv - 4 * qd - 16);
-                    }
                     const bf16x8 vf = cat(va[i], vb[i]);
 #pragma unroll
                     for (int k = 0; k < NTW; ++k)
