@@ -224,7 +224,9 @@ TAPER_API int taper_plan_resolve_slots(taper_ctx *ctx, const taper_plan *plan, i
  * `hip_stream` and returns; allocates nothing, does not synchronise.  q, kv_pages,
  * out (and lse if not NULL) are device pointers owned by the caller and must stay
  * valid until the stream has run the work.  Calls on one ctx share its workspace
- * and must be ordered on one stream.
+ * and must be ordered on one stream.  The call may be recorded into a HIP graph
+ * (stream capture) and replayed while the plan lives: the kernel leaves its
+ * counters at zero and nothing else is enqueued.
  */
 TAPER_API int taper_decode_step_attention(taper_ctx *ctx, const taper_plan *plan, const void *q /* device */,
                                 const void *kv_pages /* device */, void *out /* device */,

@@ -539,3 +539,47 @@ def test_config5_k16_every_output_two_ways(ctx_qwen):
     a, b = outs[0].float(), outs[4].float()
     assert bool(torch.isfinite(a).all()) and bool(torch.isfinite(b).all())
     assert float((a - b).abs().max()) <= 2e-2 and float((a - b).abs().mean()) <= 2e-3
+
+
+def test_layer_launches_replay_from_a_captured_graph(ctx_qwen):
+    """The attention call is one kernel launch on the caller's stream (no memset, no allocation, no host wait), so a
+    stack of layers can be captured once per plan and replayed.  Several replays, with eager work and
+    synchronisations between them, must each reproduce the eager bits (the arrival and pool counters put
+    themselves back to zero inside the kernel)."""
+    import torch
+
+    b = fill_values_numpy(structure_custom(QWEN, POOL_REQS, seed=131))
+    st = b.structure
+    n_layers = 6
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(5)
+    kvs = [torch_bf16(b.kv)] + [torch.randn(b.kv.size, generator=gen, device="cuda:0").to(torch.bfloat16) for _ in range(n_layers - 1)]
+    qs = [torch_bf16(b.q)] + [torch.randn(b.q.shape, generator=gen, device="cuda:0").to(torch.bfloat16) for _ in range(n_layers - 1)]
+    plan = ctx_qwen.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages)
+    eager = [torch.full_like(qs[0], float("nan")) for _ in range(n_layers)]
+    for l in range(n_layers):
+        ctx_qwen.decode_step_attention(plan, qs[l], kvs[l], eager[l])
+    torch.cuda.synchronize()
+    ref, _ = run_oracle(b)
+    assert_parity(f32_from_bf16_bits(bits_from_torch(eager[0])).astype(np.float64), ref, "eager layer 0")
+
+    outs = [torch.full_like(qs[0], float("nan")) for _ in range(n_layers)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for l in range(n_layers):
+                ctx_qwen.decode_step_attention(plan, qs[l], kvs[l], outs[l])
+    torch.cuda.current_stream().wait_stream(side)
+    for replay in range(4):
+        for o in outs:
+            o.fill_(float("nan"))
+        scratch = torch.full_like(qs[0], float("nan"))
+        ctx_qwen.decode_step_attention(plan, qs[replay % n_layers], kvs[replay % n_layers], scratch)  # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            assert torch.equal(outs[l].view(torch.int16), eager[l].view(torch.int16)), f"replay {replay}, layer {l}"
+    plan.free()
