@@ -223,7 +223,10 @@ TAPER_API int taper_plan_resolve_slots(taper_ctx *ctx, const taper_plan *plan, i
  * over t in shared prefix ++ private tokens of s.  Enqueues one kernel on
  * `hip_stream` and returns; allocates nothing, does not synchronise.  q, kv_pages,
  * out (and lse if not NULL) are device pointers owned by the caller and must stay
- * valid until the stream has run the work.  Calls on one ctx share its workspace
+ * valid until the stream has run the work.  Partial results of a sequence that is
+ * cut into several work items pass through half precision (normalised rows: a
+ * weighted mean of V rows), so |V| must stay below 65504 there; K and q have no
+ * such bound.  Calls on one ctx share its workspace
  * and must be ordered on one stream.  The call may be recorded into a HIP graph
  * (stream capture) and replayed while the plan lives: the kernel leaves its
  * counters at zero and nothing else is enqueued.

@@ -131,7 +131,7 @@ int ensure_workspace(taper_ctx* ctx, int64_t rows, int64_t counters) {
     const int64_t want_cnt = counters + counters / 4 + 1024;
     ctx->ws_rows = want_rows;
     ctx->ws_counters = want_cnt;
-    const size_t bytes = ws_o_offset(ctx) + (size_t)want_rows * ctx->cfg.head_dim * sizeof(float);
+    const size_t bytes = ws_o_offset(ctx) + (size_t)want_rows * ctx->cfg.head_dim * sizeof(uint16_t);
     hipError_t e = hipMalloc(&ctx->ws, bytes);
     if (e == hipSuccess) e = hipMemset(ctx->ws, 0, ws_ml_offset(ctx));
     if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -168,7 +168,7 @@ taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const vo
     a.pool_first = plan->host.part_start[plan->host.n_parts_shared + plan->host.n_parts_private];
     a.n_pool_items = plan->host.n_pool_items;
     a.ws_ml = (float2*)((char*)ctx->ws + ws_ml_offset(ctx));
-    a.ws_o = (float*)((char*)ctx->ws + ws_o_offset(ctx));
+    a.ws_o = (uint16_t*)((char*)ctx->ws + ws_o_offset(ctx));
     a.bt_stride = plan->host.bt_stride;
     a.n_seqs = plan->host.n_seqs;
     a.n_merge = (int32_t)plan->host.merge.size();

@@ -25,7 +25,7 @@ struct StepArgs {
     const int32_t* seg_page0;      // block-table entry each private segment starts at
     const int32_t* ctx_len;
     float2* ws_ml;             // [n_partial_rows] (running max in log2 units, sum)
-    float* ws_o;               // [n_partial_rows][D] unnormalised
+    uint16_t* ws_o;            // [n_partial_rows][D] half precision, each row divided by its own sum
     int32_t* counters;         // [n_seqs][n_kv_heads] partials delivered so far; zero between launches
     int32_t* pool_ctr;         // [n_kv_heads] pool items taken so far; zero between launches
     int32_t pool_first, n_pool_items;  // the pool: items [pool_first, pool_first + n_pool_items)

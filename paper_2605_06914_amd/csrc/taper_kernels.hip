@@ -95,15 +95,19 @@ DEV float2 coherent_load2(const float* p) {
     const unsigned long long v = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return make_float2(__uint_as_float((unsigned)v), __uint_as_float((unsigned)(v >> 32)));
 }
-DEV void coherent_store4(float* p, f32x4 v) {
-    coherent_store2(p, v[0], v[1]);
-    coherent_store2(p + 2, v[2], v[3]);
+// The accumulator part of a partial row travels normalised (divided by the row's own sum, so that
+// it is a weighted mean of V rows and cannot leave the half-precision range unless V itself does)
+// and in half precision: four values per 8-byte access, half the workspace traffic, and 11 bits
+// of mantissa beside the 8 that the bf16 result keeps.
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+DEV void partial_store4(uint16_t* p, f32x4 v) {
+    const f16x4 h = __builtin_convertvector(v, f16x4);
+    __hip_atomic_store((unsigned long long*)p, __builtin_bit_cast(unsigned long long, h), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-DEV f32x4 coherent_load4(const float* p) {
-    const float2 a = coherent_load2(p), b = coherent_load2(p + 2);
-    f32x4 r = {a.x, a.y, b.x, b.y};
-    return r;
+DEV unsigned long long partial_load4_raw(const uint16_t* p) {
+    return __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+DEV f32x4 partial_unpack4(unsigned long long raw) { return __builtin_convertvector(__builtin_bit_cast(f16x4, raw), f32x4); }
 // Every earlier vector memory operation of this wave has completed, in particular its
 // write-through stores of partial rows.  (A workgroup-scope release fence does not wait for
 // global stores on this target, and nothing weaker than a full wait orders the stores
@@ -200,25 +204,25 @@ DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const i
         for (int u = 0; u < U; ++u) acc[u] = (f32x4)(0.f);
         for (int e = e0; e < e1; e += R) {
             float2 ml[R];
-            f32x4 o[R][U];
+            unsigned long long o[R][U];  // four half-precision values each, unpacked when they are used
 #pragma unroll
             for (int k = 0; k < R; ++k) {
                 ml[k] = make_float2(-INFINITY, 0.f);
 #pragma unroll
-                for (int u = 0; u < U; ++u) o[k][u] = (f32x4)(0.f);
+                for (int u = 0; u < U; ++u) o[k][u] = 0ull;
                 if (e + k < e1) {
                     // the entry is the same for every lane: its rows' base address goes into scalar
                     // registers and each load needs only a 32-bit per-lane offset
                     const taper_merge_entry me = merge_entry(a, mm, e + k);
                     const int64_t row0 = (int64_t)__builtin_amdgcn_readfirstlane(me.first_row) +
                                          (int64_t)hk * __builtin_amdgcn_readfirstlane(me.rows_per_head);
-                    const float* op = a.ws_o + row0 * D;
+                    const uint16_t* op = a.ws_o + row0 * D;
                     const float2* mp = a.ws_ml + row0;
                     const unsigned jo = okr ? j : 0;
                     const float2 v = coherent_load2((const float*)(mp + jo));
                     if (okr) ml[k] = v;
 #pragma unroll
-                    for (int u = 0; u < U; ++u) o[k][u] = coherent_load4(op + (jo * D + 4u * (c0 + LPR * u)));
+                    for (int u = 0; u < U; ++u) o[k][u] = partial_load4_raw(op + (jo * D + 4u * (c0 + LPR * u)));
                 }
             }
             float mn = M;
@@ -230,10 +234,10 @@ DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const i
             for (int u = 0; u < U; ++u) acc[u] *= keep;
 #pragma unroll
             for (int k = 0; k < R; ++k) {
-                const float w = fast_exp2(ml[k].x - mn);
-                L += w * ml[k].y;
+                const float w = fast_exp2(ml[k].x - mn) * ml[k].y;  // (the row was stored divided by its sum)
+                L += w;
 #pragma unroll
-                for (int u = 0; u < U; ++u) acc[u] += w * o[k][u];
+                for (int u = 0; u < U; ++u) acc[u] += w * partial_unpack4(o[k][u]);
             }
             M = mn;
         }
@@ -424,7 +428,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
                 continue;
             }
             const int64_t slot = (int64_t)item.part_base + hk * g + r;
-            coherent_store4(a.ws_o + slot * D + 4 * d4, acc);
+            partial_store4(a.ws_o + slot * D + 4 * d4, acc * (1.0f / L));
             if (d4 == 0) coherent_store2((float*)(a.ws_ml + slot), M, L);
         }
         if (sole) {
@@ -684,8 +688,9 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
                 if (r < R) {
                     const int64_t slot = (int64_t)item.part_base + (int64_t)hk * R + r;
                     if (qd == 0) coherent_store2((float*)(a.ws_ml + slot), m[k], lt);
+                    const float inv = 1.0f / lt;
 #pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) coherent_store4(a.ws_o + slot * D + 16 * dt + 4 * qd, O[k][dt]);
+                    for (int dt = 0; dt < DT; ++dt) partial_store4(a.ws_o + slot * D + 16 * dt + 4 * qd, O[k][dt] * inv);
                 }
             }
         }
@@ -894,8 +899,9 @@ DEV void shared_path_wide(const StepArgs& a, const int part, const int hk, Share
                 if (r < R) {
                     const int64_t slot = (int64_t)item.part_base + (int64_t)hk * R + r;
                     if (qd == 0) coherent_store2((float*)(a.ws_ml + slot), m[k], lt);
+                    const float inv = 1.0f / lt;
 #pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) coherent_store4(a.ws_o + slot * D + 16 * dt + 4 * qd, O[k][dt]);
+                    for (int dt = 0; dt < DT; ++dt) partial_store4(a.ws_o + slot * D + 16 * dt + 4 * qd, O[k][dt] * inv);
                 }
             }
         }
