@@ -583,3 +583,21 @@ def test_layer_launches_replay_from_a_captured_graph(ctx_qwen):
         for l in range(n_layers):
             assert torch.equal(outs[l].view(torch.int16), eager[l].view(torch.int16)), f"replay {replay}, layer {l}"
     plan.free()
+
+
+@pytest.mark.parametrize("log2_scale", [9, 13])
+def test_large_values_of_v_pass_through_the_partials(ctx_qwen, log2_scale):
+    """Partial rows between workgroups are half precision after normalisation, so they stay inside the range of
+    V itself: V scaled by 2^9 and 2^13 (|V| up to about 3e4, below the half-precision limit) must give the
+    unscaled result times the same power of two, up to the rounding of values that were subnormal before."""
+    b = fill_values_numpy(structure_custom(QWEN, POOL_REQS, seed=141))
+    base, _, _ = run_gpu(ctx_qwen, b, target_workgroups=2048, min_share_tokens=1)
+    st, sh = b.structure, b.structure.shape
+    pv = PoolView(sh.n_kv_heads, sh.head_dim, sh.page_size)
+    kv = b.kv.reshape(st.n_pool_pages, 2, sh.n_kv_heads, sh.page_size * sh.head_dim)
+    v = f32_from_bf16_bits(kv[:, 1]) * np.float32(2.0 ** log2_scale)  # exact: a power of two
+    kv[:, 1] = bf16_bits_from_f32(v)
+    assert np.abs(v).max() < 65504
+    got, _, _ = run_gpu(ctx_qwen, b, target_workgroups=2048, min_share_tokens=1)
+    assert np.isfinite(got).all()
+    assert np.max(np.abs(got / 2.0 ** log2_scale - base)) <= 1e-3
