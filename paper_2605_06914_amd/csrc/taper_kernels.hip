@@ -16,8 +16,8 @@
 //
 // Softmax state per query row (one lane column): running max m in log2 units
 // (scale*log2(e) folded in), running sum l, unnormalised O.  Partials of the KV
-// chunks of a sequence are combined through their (m, l) by the workgroup that
-// delivers the sequence's last partial (merge_rows).
+// chunks of a sequence (m, l in fp32; O / l in half precision) are combined through
+// their (m, l) by the workgroup that delivers the sequence's last partial (merge_rows).
 #include "taper_internal.h"
 
 namespace taper {
