@@ -601,3 +601,21 @@ def test_large_values_of_v_pass_through_the_partials(ctx_qwen, log2_scale):
     got, _, _ = run_gpu(ctx_qwen, b, target_workgroups=2048, min_share_tokens=1)
     assert np.isfinite(got).all()
     assert np.max(np.abs(got / 2.0 ** log2_scale - base)) <= 1e-3
+
+
+def test_five_thousand_sequences(ctx_qwen):
+    """A step far wider than the paper's batches (5000 sequences: short serial requests and two-branch requests
+    with tiny prefixes): counters, merge lists and partial rows are indexed per sequence and must scale."""
+    rng = np.random.default_rng(151)
+    reqs = []
+    for _ in range(4000):
+        reqs.append((int(rng.integers(1, 48)), [0]))
+    for _ in range(500):
+        reqs.append((int(rng.integers(1, 80)), [int(rng.integers(0, 20)), int(rng.integers(0, 20))]))
+    b = fill_values_numpy(structure_custom(QWEN, reqs, seed=151))
+    assert b.structure.n_seqs == 5000
+    ref, ref_lse = run_oracle(b)
+    for kw in ({}, dict(share_prefix=0, target_workgroups=4096)):
+        got, lse, _ = run_gpu(ctx_qwen, b, **kw)
+        assert_parity(got, ref, f"5000 sequences {kw}")
+        assert np.max(np.abs(lse - ref_lse)) <= 2e-3
