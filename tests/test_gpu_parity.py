@@ -67,7 +67,7 @@ def test_ragged_qwen_shape(ctx_qwen, share, target):
     assert np.max(np.abs(lse - ref_lse)) <= 2e-3
 
 
-@pytest.mark.parametrize("width", [2, 3, 16, 17, 24, 25, 40])
+@pytest.mark.parametrize("width", [2, 3, 16, 17, 24, 25, 40, 65, 130])
 def test_wide_requests(ctx_qwen, width):
     """Branch widths around the limits of one workgroup's row tiles (16 rows per
     tile, 12 tiles per workgroup, wider requests cut into sub-groups)."""
