@@ -21,6 +21,6 @@ def test_the_package_never_imports_the_oracle_or_working_files():
             if f.endswith((".py", ".cpp", ".h", ".hip")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(import|from)\s+oracle\b", text, re.M), f
-                assert "_work" not in text, f
+                assert not re.search(r"(?<![A-Za-z0-9])_work(?![A-Za-z0-9_])", text), f
     for f in ("bench.py", "__graft_entry__.py"):
-        assert "_work" not in open(os.path.join(ROOT, f)).read(), f
+        assert not re.search(r"(?<![A-Za-z0-9])_work(?![A-Za-z0-9_])", open(os.path.join(ROOT, f)).read()), f
