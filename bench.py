@@ -456,7 +456,14 @@ def main():
             "config": {"workload": f"config5 admission sweep x {n_layers} layers, value quoted at k={top['k']} "
                                    f"({args.sweep_pools} distinct KV pools cycled over the layers)",
                        "n_layers": n_layers},
-            "step_latency_vs_admitted_branches": rows}))
+            "step_latency_vs_admitted_branches": rows,
+            # the widest point: the step is n_layers launches back to back (plan build overlapped), so the
+            # launch duration is the step time over the layer count; kernel trace and HBM counters of this
+            # point are in profiles/decode_kernel_sweep_k16.md
+            "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": top["gbps_unique"], "peak": HBM_PEAK_GBPS,
+                         "unit": "GB/s", "frac": top["frac_of_hbm_peak"], "traffic": None,
+                         "avg_launch_us": round(top["ms_per_step"] * 1e3 / n_layers, 2), "k": top["k"]},
+            "cpu_baseline": None}))
         return
     st = make_structure(args.workload)
     sh = st.shape
