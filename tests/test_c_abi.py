@@ -18,3 +18,36 @@ def test_headers_are_c99_and_a_c_program_can_use_the_library(tmp_path):
         env["LD_LIBRARY_PATH"] = d + ":" + env.get("LD_LIBRARY_PATH", "")
     out = subprocess.run([str(exe)], env=env, capture_output=True, text=True, timeout=60)
     assert out.returncode == 0 and out.stdout.strip() == "ok", out.stdout + out.stderr
+
+
+def test_ctypes_structures_mirror_the_headers_field_by_field(tmp_path):
+    """Every structure the binding declares has the size the C compiler gives it, and every field sits at
+    the same offset with the same size (a reordered or missing field would silently shift the rest)."""
+    import ctypes
+
+    from paper_2605_06914_amd import binding
+
+    names = ["taper_attn_config", "taper_work_item", "taper_merge_entry", "taper_plan_view", "taper_plan_options",
+             "taper_probe_result", "taper_predictor", "taper_admission_options", "taper_admission_result"]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "taper_attn.h"', '#include "taper_admission.h"',
+             'int main(void) {']
+    for n in names:
+        cls = getattr(binding, n)
+        lines.append(f'    printf("{n} %zu\\n", sizeof({n}));')
+        for f, _ in cls._fields_:
+            lines.append(f'    printf("{n}.{f} %zu %zu\\n", offsetof({n}, {f}), sizeof((({n} *)0)->{f}));')
+    lines += ['    return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines) + "\n")
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    seen = {}
+    for line in subprocess.run([str(exe)], capture_output=True, text=True, timeout=60).stdout.splitlines():
+        key, *vals = line.split()
+        seen[key] = tuple(int(v) for v in vals)
+    for n in names:
+        cls = getattr(binding, n)
+        assert seen[n] == (ctypes.sizeof(cls),), (n, seen[n], ctypes.sizeof(cls))
+        for f, _ in cls._fields_:
+            d = getattr(cls, f)
+            assert seen[f"{n}.{f}"] == (d.offset, d.size), (n, f, seen[f"{n}.{f}"], d.offset, d.size)
