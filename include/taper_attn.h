@@ -31,7 +31,7 @@
  *          i.e. V is stored transposed in groups of 4 tokens: [page_size/4][head_dim][4].
  *          Both are what a 64-lane MFMA operand fetch reads with unit stride.
  *          Slots past a segment's length and unreferenced pages may hold any
- *          finite values; results do not depend on them.
+ *          bit pattern, NaN and Inf included; results do not depend on them.
  * Grouped-query attention: query head h reads KV head h / (n_q_heads / n_kv_heads).
  *
  * ---------------------------------------------------------------- the batch
@@ -72,6 +72,22 @@ typedef enum {
     TAPER_ENOMEM = -6  /* host or device allocation failed                         */
 } taper_status;
 
+/*
+ * How the partial result of one work item travels to the workgroup that merges a
+ * sequence's partials (a sequence whose context is cut into several work items;
+ * one that is a single item never goes through a partial).  Accumulation is fp32
+ * in registers either way, and so are the running max and sum of every partial.
+ */
+typedef enum {
+    TAPER_PARTIAL_F16_SCALED = 0, /* default: the accumulator row, divided by its own sum (a weighted mean
+                                     of V rows) and by a power of two that brings its largest magnitude
+                                     into [0.5, 1), in half precision; the power of two travels in fp32
+                                     beside the running max and sum.  Error 2^-12 of the row's largest
+                                     element, whatever the magnitude of V (no range limit); half the
+                                     workspace traffic of fp32 rows                                        */
+    TAPER_PARTIAL_F32 = 1         /* the accumulator row divided by its own sum, in fp32                   */
+} taper_partial_format;
+
 typedef struct {
     int n_q_heads;  /* 64 (Qwen3-32B shape, App. D) or any multiple of n_kv_heads  */
     int n_kv_heads; /* 8                                                            */
@@ -80,9 +96,10 @@ typedef struct {
     float scale;    /* softmax scale, normally 1/sqrt(head_dim)                     */
     int device;     /* HIP device ordinal; -1 = host-only context: plans can be
                        built, validated and exported, device calls return TAPER_EHIP */
+    int partial_format; /* taper_partial_format; 0 = default                        */
 } taper_attn_config;
 
-typedef struct taper_ctx taper_ctx;   /* owns the partials workspace              */
+typedef struct taper_ctx taper_ctx;   /* owns the partials workspaces             */
 typedef struct taper_plan taper_plan; /* owns host + device copies of the step's integer metadata */
 
 /* One unit of KV streaming: n_tokens tokens starting at block-table entry page0 of
@@ -128,6 +145,9 @@ typedef struct {
     int64_t n_partial_rows;
     int64_t tokens_unique;  /* sum over requests of prefix_len + sum over sequences of suffix_len */
     int64_t tokens_logical; /* sum over sequences of prefix_len + suffix_len: L_context of §3.2   */
+    int32_t workspace_id;   /* which of the context's workspaces the plan is bound to (counts from 1 in
+                               order of creation); it never changes while the plan lives          */
+    int64_t workspace_rows; /* partial rows that workspace holds                                  */
 } taper_plan_view;
 
 typedef struct {
@@ -168,12 +188,38 @@ TAPER_API int taper_create(const taper_attn_config *cfg /* host */, taper_ctx **
 TAPER_API void taper_destroy(taper_ctx *ctx);
 
 /*
+ * Workspaces.  The partial rows and arrival counters of a launch live in a
+ * workspace owned by the context.  A plan is bound, when it is built, to the
+ * context's current workspace if that is large enough; otherwise a larger one is
+ * allocated BESIDE it and becomes current.  A workspace is never freed or moved
+ * while a plan bound to it lives, so launches already enqueued, and HIP graphs
+ * captured from a plan, stay valid for as long as their plan does, whatever is
+ * built afterwards.  Superseded workspaces no plan is bound to any more are
+ * released at the next growth (after a device synchronisation) and in
+ * taper_destroy; in the steady state nothing is allocated, freed or synchronised.
+ *
+ * taper_reserve sizes the current workspace ahead of time for plans of up to
+ * max_seqs sequences and max_partial_rows partial rows (n_partial_rows of a
+ * representative plan's view; a host-only context computes it without a GPU), so
+ * that no later taper_plan_build allocates.  TAPER_EINVAL for negative sizes,
+ * TAPER_ENOMEM when the device allocation fails.  On a host-only context only
+ * the bookkeeping is done.
+ *
+ * The arrival and pool counters of a workspace are zero between launches (every
+ * launch leaves them so).  They are cleared when a workspace is created, and
+ * again, on the stream of the next taper_plan_build or launch, after any call on
+ * the context has reported a HIP error.
+ */
+TAPER_API int taper_reserve(taper_ctx *ctx, int max_seqs, int64_t max_partial_rows);
+
+/*
  * Index resolution for one decode step (paper: the engine's batch formation
  * precedes the forward pass, App. D "Serving engine"; which pages each query row
  * reads follows §3.1).  Validates the batch, derives the request CSR, page counts,
  * the list of KV chunks and the merge map, copies them to the device on
- * `hip_stream` (unless the context is host-only) and grows the context's
- * workspace if needed.  The host arrays are only read during the call.  One plan
+ * `hip_stream` (unless the context is host-only) and binds the plan to a
+ * workspace (see taper_reserve: a larger one is allocated beside the current one
+ * if the plan needs it).  The host arrays are only read during the call.  One plan
  * serves every layer of the step.  Not safe to call concurrently on one ctx.
  * Plans must be freed before their context is destroyed; a freed plan's buffers
  * are recycled by later plans of the same context, ordered on the stream.
@@ -224,12 +270,12 @@ TAPER_API int taper_plan_resolve_slots(taper_ctx *ctx, const taper_plan *plan, i
  * `hip_stream` and returns; allocates nothing, does not synchronise.  q, kv_pages,
  * out (and lse if not NULL) are device pointers owned by the caller and must stay
  * valid until the stream has run the work.  Partial results of a sequence that is
- * cut into several work items pass through half precision (normalised rows: a
- * weighted mean of V rows), so |V| must stay below 65504 there; K and q have no
- * such bound.  Calls on one ctx share its workspace
- * and must be ordered on one stream.  The call may be recorded into a HIP graph
- * (stream capture) and replayed while the plan lives: the kernel leaves its
- * counters at zero and nothing else is enqueued.
+ * cut into several work items travel in the context's taper_partial_format.
+ * Calls on one ctx share its workspaces and must be ordered on one stream.  The
+ * call may be recorded into a HIP graph (stream capture) and replayed while the
+ * plan lives (the graph holds the addresses of the plan's device arrays and of the
+ * workspace the plan is bound to, both of which live as long as the plan): the
+ * kernel leaves its counters at zero and nothing else is enqueued.
  */
 TAPER_API int taper_decode_step_attention(taper_ctx *ctx, const taper_plan *plan, const void *q /* device */,
                                 const void *kv_pages /* device */, void *out /* device */,

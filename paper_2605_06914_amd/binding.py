@@ -26,13 +26,14 @@ EXPORTED = [
     "taper_plan_build_segments", "taper_append_slots", "taper_kv_append", "taper_branch_blocks",
     "taper_predictor_fit", "taper_predictor_eval", "taper_predictor_mape", "taper_window_create",
     "taper_window_destroy", "taper_window_push", "taper_window_size", "taper_window_fit", "taper_admit_step",
-    "taper_stream_read_probe",
+    "taper_stream_read_probe", "taper_reserve",
 ]
 
 
 class taper_attn_config(ctypes.Structure):
     _fields_ = [("n_q_heads", ctypes.c_int), ("n_kv_heads", ctypes.c_int), ("head_dim", ctypes.c_int),
-                ("page_size", ctypes.c_int), ("scale", ctypes.c_float), ("device", ctypes.c_int)]
+                ("page_size", ctypes.c_int), ("scale", ctypes.c_float), ("device", ctypes.c_int),
+                ("partial_format", ctypes.c_int)]
 
 
 class taper_work_item(ctypes.Structure):
@@ -56,7 +57,8 @@ class taper_plan_view(ctypes.Structure):
                 ("n_parts_shared", ctypes.c_int32), ("n_parts_private", ctypes.c_int32), ("part_start", _I32P),
                 ("merge_start", _I32P), ("merge", ctypes.POINTER(taper_merge_entry)),
                 ("n_partial_rows", ctypes.c_int64), ("tokens_unique", ctypes.c_int64),
-                ("tokens_logical", ctypes.c_int64)]
+                ("tokens_logical", ctypes.c_int64), ("workspace_id", ctypes.c_int32),
+                ("workspace_rows", ctypes.c_int64)]
 
 
 class taper_plan_options(ctypes.Structure):
@@ -89,6 +91,7 @@ class taper_admission_result(ctypes.Structure):
 
 
 UTILITY_KINDS = {"linear": 0, "concave": 1, "table": 2}
+PARTIAL_FORMATS = {"f16_scaled": 0, "f32": 1}
 
 
 class TaperError(RuntimeError):
@@ -117,6 +120,7 @@ def load_library() -> ctypes.CDLL:
     lib.taper_create.argtypes = [ctypes.POINTER(taper_attn_config), ctypes.POINTER(vp)]
     lib.taper_destroy.argtypes = [vp]
     lib.taper_destroy.restype = None
+    lib.taper_reserve.argtypes = [vp, ci, i64]
     lib.taper_plan_build.argtypes = [vp, ci, vp, ci, vp, vp, vp, i64, ctypes.POINTER(taper_plan_options), vp,
                                      ctypes.POINTER(vp)]
     lib.taper_plan_build_segments.argtypes = [vp, ci, vp, ci, vp, vp, vp, vp, i64, ctypes.POINTER(taper_plan_options), vp,
@@ -222,7 +226,8 @@ class Plan:
                     n_pool_items=v.n_pool_items, n_parts_shared=v.n_parts_shared, n_parts_private=v.n_parts_private,
                     part_start=arr(v.part_start, n_parts + 1), merge_start=arr(v.merge_start, S + 1), merge=merge,
                     n_partial_rows=int(v.n_partial_rows), tokens_unique=int(v.tokens_unique),
-                    tokens_logical=int(v.tokens_logical))
+                    tokens_logical=int(v.tokens_logical), workspace_id=int(v.workspace_id),
+                    workspace_rows=int(v.workspace_rows))
 
     def resolve_slots_host(self, stride: int) -> np.ndarray:
         S = self.export()["n_seqs"]
@@ -238,10 +243,11 @@ class Context:
     """taper_ctx: shape + workspace.  device=-1 gives a host-only context."""
 
     def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, page_size: int = 16,
-                 scale: Optional[float] = None, device: int = 0):
+                 scale: Optional[float] = None, device: int = 0, partial_format="f16_scaled"):
         lib = load_library()
+        pf = PARTIAL_FORMATS[partial_format] if isinstance(partial_format, str) else int(partial_format)
         cfg = taper_attn_config(n_q_heads, n_kv_heads, head_dim, page_size,
-                                float(scale if scale is not None else head_dim ** -0.5), device)
+                                float(scale if scale is not None else head_dim ** -0.5), device, pf)
         h = ctypes.c_void_p()
         _check(lib.taper_create(ctypes.byref(cfg), ctypes.byref(h)))
         self._h = h.value
@@ -257,6 +263,10 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def reserve(self, max_seqs: int, max_partial_rows: int):
+        """Size the workspace ahead of time so that no later plan_build allocates."""
+        _check(load_library().taper_reserve(self._h, int(max_seqs), int(max_partial_rows)))
 
     def plan_build(self, block_table, branch_group, prefix_len, suffix_len, n_pool_pages: int,
                    target_workgroups: int = 0, share_prefix: bool = True, max_branches_per_item: int = 0,

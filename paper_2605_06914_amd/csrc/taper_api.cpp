@@ -47,31 +47,51 @@ struct PlanBuffers {
     hipEvent_t uploaded = nullptr;  // recorded after the host-to-device copy
 };
 
+// Partial rows and counters of launches: [counters] int32 | [rows] float4 (m, l, row scale, -) | [rows][D] rows.
+// A plan is bound to one workspace for its whole life, and a workspace lives at least as long as
+// the plans bound to it: launches in flight and captured graphs keep valid addresses whatever
+// is built later.
+struct Workspace {
+    void* base = nullptr;  // null on a host-only context (bookkeeping only)
+    int64_t rows = 0, counters = 0;
+    size_t ml_off = 0, o_off = 0, bytes = 0;
+    int refs = 0;  // live plans bound to it
+    int id = 0;
+};
+
+// Where the device arrays of a plan sit (inside a plan's own buffer, or inside the static scratch array).
+struct DeviceImage {
+    const int32_t* bt = nullptr;
+    const taper_work_item* items = nullptr;
+    const int32_t* part_start = nullptr;
+    const int32_t* merge_start = nullptr;
+    const taper_merge_entry* merge = nullptr;
+    const int32_t* prefix_len = nullptr;
+    const int32_t* seg_start = nullptr;
+    const int32_t* seg_len = nullptr;
+    const int32_t* seg_page0 = nullptr;
+    const int32_t* ctx_len = nullptr;
+};
+
 struct taper_ctx {
     taper_attn_config cfg;
     bool host_only = false;
-    void* ws = nullptr;  // workspace: [counters] int32 | [rows] float2 (m, l) | [rows][D] float
-    int64_t ws_rows = 0;
-    int64_t ws_counters = 0;
+    std::vector<Workspace*> workspaces;  // the last one is current; earlier ones wait for their plans to go
+    int next_workspace_id = 1;
+    bool counters_suspect = false;  // a call reported a HIP error: clear every workspace's counters before the next launch
     std::vector<PlanBuffers> free_buffers;
     int default_workgroups = 0;  // two resident workgroups per compute unit of the device (0: the builder's own default)
+#ifdef TAPER_WG_TRACE
+    long long* trace = nullptr;
+#endif
 };
 
 struct taper_plan {
     taper_ctx* ctx = nullptr;
     taper::HostPlan host;
     PlanBuffers buf;
-    // device pointers into `dev`
-    const int32_t* d_bt = nullptr;
-    const taper_work_item* d_items = nullptr;
-    const int32_t* d_part_start = nullptr;
-    const int32_t* d_merge_start = nullptr;
-    const taper_merge_entry* d_merge = nullptr;
-    const int32_t* d_prefix_len = nullptr;
-    const int32_t* d_seg_start = nullptr;
-    const int32_t* d_seg_len = nullptr;
-    const int32_t* d_seg_page0 = nullptr;
-    const int32_t* d_ctx_len = nullptr;
+    DeviceImage img;
+    Workspace* ws = nullptr;
 };
 
 namespace {
@@ -112,88 +132,195 @@ int acquire_buffers(taper_ctx* ctx, size_t bytes, PlanBuffers* out) {
     return TAPER_OK;
 }
 
-size_t ws_ml_offset(const taper_ctx* ctx) { return align_up((size_t)ctx->ws_counters * sizeof(int32_t), 256); }
-size_t ws_o_offset(const taper_ctx* ctx) {
-    return ws_ml_offset(ctx) + align_up((size_t)ctx->ws_rows * sizeof(float2), 256);
+// The arrays of a host plan as one image: bt | items | part_start | merge_start | merge | prefix_len |
+// seg_start | ctx_len | seg_len | seg_page0, each piece 256-byte aligned.
+struct ImagePiece {
+    const void* src;
+    size_t bytes, off;
+};
+size_t layout_image(const taper::HostPlan& h, ImagePiece (&pieces)[10]) {
+    const ImagePiece init[10] = {
+        {h.block_table.data(), h.block_table.size() * sizeof(int32_t), 0},
+        {h.items.data(), h.items.size() * sizeof(taper_work_item), 0},
+        {h.part_start.data(), h.part_start.size() * sizeof(int32_t), 0},
+        {h.merge_start.data(), h.merge_start.size() * sizeof(int32_t), 0},
+        {h.merge.data(), h.merge.size() * sizeof(taper_merge_entry), 0},
+        {h.prefix_len.data(), h.prefix_len.size() * sizeof(int32_t), 0},
+        {h.seg_start.data(), h.seg_start.size() * sizeof(int32_t), 0},
+        {h.ctx_len.data(), h.ctx_len.size() * sizeof(int32_t), 0},
+        {h.seg_len.data(), h.seg_len.size() * sizeof(int32_t), 0},
+        {h.seg_page0.data(), h.seg_page0.size() * sizeof(int32_t), 0},
+    };
+    size_t total = 0;
+    for (int i = 0; i < 10; ++i) {
+        pieces[i] = init[i];
+        pieces[i].off = total;
+        total += align_up(std::max<size_t>(pieces[i].bytes, 16), 256);
+    }
+    return total;
+}
+void write_image(const ImagePiece (&pieces)[10], void* host_dst) {
+    for (const ImagePiece& p : pieces)
+        if (p.bytes) std::memcpy((char*)host_dst + p.off, p.src, p.bytes);
+}
+DeviceImage bind_image(const ImagePiece (&pieces)[10], void* dev_base) {
+    char* d = (char*)dev_base;
+    DeviceImage m;
+    m.bt = (const int32_t*)(d + pieces[0].off);
+    m.items = (const taper_work_item*)(d + pieces[1].off);
+    m.part_start = (const int32_t*)(d + pieces[2].off);
+    m.merge_start = (const int32_t*)(d + pieces[3].off);
+    m.merge = (const taper_merge_entry*)(d + pieces[4].off);
+    m.prefix_len = (const int32_t*)(d + pieces[5].off);
+    m.seg_start = (const int32_t*)(d + pieces[6].off);
+    m.ctx_len = (const int32_t*)(d + pieces[7].off);
+    m.seg_len = (const int32_t*)(d + pieces[8].off);
+    m.seg_page0 = (const int32_t*)(d + pieces[9].off);
+    return m;
 }
 
-// Grows the workspace to hold `rows` partial rows and `counters` arrival counters.
-// Counters are zero whenever no launch is in flight: each launch leaves them so.
-int ensure_workspace(taper_ctx* ctx, int64_t rows, int64_t counters) {
-    if (rows <= ctx->ws_rows && counters <= ctx->ws_counters) return TAPER_OK;
-    if (ctx->ws) {
-        HIP_TRY(hipDeviceSynchronize());
-        HIP_TRY(hipFree(ctx->ws));
-        ctx->ws = nullptr;
-        ctx->ws_rows = ctx->ws_counters = 0;
+size_t partial_row_bytes(const taper_attn_config& cfg) {
+    return (size_t)cfg.head_dim * (cfg.partial_format == TAPER_PARTIAL_F32 ? sizeof(float) : sizeof(uint16_t));
+}
+// Offsets of the three parts of a workspace of `rows` partial rows and `counters` counters; returns its size.
+size_t layout_workspace(const taper_attn_config& cfg, int64_t rows, int64_t counters, size_t* ml_off, size_t* o_off) {
+    *ml_off = align_up((size_t)counters * sizeof(int32_t), 256);
+    *o_off = *ml_off + align_up((size_t)rows * sizeof(float4), 256);
+    return *o_off + align_up((size_t)rows * partial_row_bytes(cfg), 256);
+}
+int64_t counters_needed(const taper_attn_config& cfg, int n_seqs) { return ((int64_t)n_seqs + 1) * cfg.n_kv_heads; }
+
+void release_workspace(Workspace* w) {
+    if (w->base) (void)hipFree(w->base);
+    delete w;
+}
+
+// The context's current workspace if it holds `rows` partial rows and `counters` counters, else a new,
+// larger one beside it (the old one stays for the plans bound to it).
+int current_workspace(taper_ctx* ctx, int64_t rows, int64_t counters, bool headroom, Workspace** out) {
+    Workspace* cur = ctx->workspaces.empty() ? nullptr : ctx->workspaces.back();
+    if (cur && rows <= cur->rows && counters <= cur->counters) {
+        *out = cur;
+        return TAPER_OK;
     }
-    const int64_t want_rows = rows + rows / 4 + 1024;  // head-room so steady-state steps do not reallocate
-    const int64_t want_cnt = counters + counters / 4 + 1024;
-    ctx->ws_rows = want_rows;
-    ctx->ws_counters = want_cnt;
-    const size_t bytes = ws_o_offset(ctx) + (size_t)want_rows * ctx->cfg.head_dim * sizeof(uint16_t);
-    hipError_t e = hipMalloc(&ctx->ws, bytes);
-    if (e == hipSuccess) e = hipMemset(ctx->ws, 0, ws_ml_offset(ctx));
-    if (e == hipSuccess) e = hipDeviceSynchronize();
-    if (e != hipSuccess) {
-        if (ctx->ws) (void)hipFree(ctx->ws);
-        ctx->ws = nullptr;
-        ctx->ws_rows = ctx->ws_counters = 0;
-        g_last_error = std::string("workspace allocation: ") + hipGetErrorString(e);
-        return TAPER_ENOMEM;
+    // growth: the only moment anything is freed (superseded workspaces that no plan is bound to any more)
+    bool synced = false;
+    for (size_t i = 0; i < ctx->workspaces.size();) {
+        Workspace* w = ctx->workspaces[i];
+        if (w->refs > 0) {
+            ++i;
+            continue;
+        }
+        if (w->base && !synced) {  // launches of plans already freed may still be running
+            HIP_TRY(hipDeviceSynchronize());
+            synced = true;
+        }
+        release_workspace(w);
+        ctx->workspaces.erase(ctx->workspaces.begin() + i);
     }
+    Workspace* w = new (std::nothrow) Workspace();
+    if (!w) return fail(TAPER_ENOMEM, "host allocation failed");
+    if (cur) {  // never smaller than what it replaces
+        rows = std::max(rows, cur->rows);
+        counters = std::max(counters, cur->counters);
+    }
+    w->rows = headroom ? rows + rows / 4 + 1024 : rows;  // head-room so that slowly growing steps do not reallocate
+    w->counters = headroom ? counters + counters / 4 + 1024 : counters;
+    w->bytes = layout_workspace(ctx->cfg, w->rows, w->counters, &w->ml_off, &w->o_off);
+    w->id = ctx->next_workspace_id++;
+    if (!ctx->host_only) {
+        hipError_t e = hipSetDevice(ctx->cfg.device);
+        if (e == hipSuccess) e = hipMalloc(&w->base, w->bytes);
+        if (e == hipSuccess) e = hipMemset(w->base, 0, w->ml_off);  // counters start at zero
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) {
+            g_last_error = std::string("workspace allocation: ") + hipGetErrorString(e);
+            release_workspace(w);
+            return TAPER_ENOMEM;
+        }
+    }
+    ctx->workspaces.push_back(w);
+    *out = w;
     return TAPER_OK;
 }
 
-taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const void* q, const void* kv, void* out,
-                          float* lse) {
+// After a HIP error the counters of a workspace may have been left non-zero by a launch that did not
+// finish; every later launch would then merge too early or never.  Clears them on `s`.
+int recover_counters(taper_ctx* ctx, hipStream_t s) {
+    if (!ctx->counters_suspect || ctx->host_only) return TAPER_OK;
+    for (Workspace* w : ctx->workspaces)
+        if (w->base) HIP_TRY(hipMemsetAsync(w->base, 0, w->ml_off, s));
+    ctx->counters_suspect = false;
+    return TAPER_OK;
+}
+
+taper::StepArgs make_args(const taper_ctx* ctx, const taper::HostPlan& h, const DeviceImage& img, void* ws_base,
+                          size_t ml_off, size_t o_off, const void* q, const void* kv, void* out, float* lse) {
     taper::StepArgs a;
     std::memset(&a, 0, sizeof a);
     a.q = q;
     a.kv = kv;
     a.out = out;
     a.lse = lse;
-    a.bt = plan->d_bt;
-    a.items = plan->d_items;
-    a.part_start = plan->d_part_start;
-    a.merge_start = plan->d_merge_start;
-    a.merge = plan->d_merge;
-    a.prefix_len = plan->d_prefix_len;
-    a.seg_start = plan->d_seg_start;
-    a.seg_len = plan->d_seg_len;
-    a.seg_page0 = plan->d_seg_page0;
-    a.ctx_len = plan->d_ctx_len;
-    a.counters = (int32_t*)ctx->ws;
-    a.pool_ctr = a.counters + (int64_t)plan->host.n_seqs * ctx->cfg.n_kv_heads;
-    a.pool_first = plan->host.part_start[plan->host.n_parts_shared + plan->host.n_parts_private];
-    a.n_pool_items = plan->host.n_pool_items;
-    a.ws_ml = (float2*)((char*)ctx->ws + ws_ml_offset(ctx));
-    a.ws_o = (uint16_t*)((char*)ctx->ws + ws_o_offset(ctx));
-    a.bt_stride = plan->host.bt_stride;
-    a.n_seqs = plan->host.n_seqs;
-    a.n_merge = (int32_t)plan->host.merge.size();
+    a.bt = img.bt;
+    a.items = img.items;
+    a.part_start = img.part_start;
+    a.merge_start = img.merge_start;
+    a.merge = img.merge;
+    a.prefix_len = img.prefix_len;
+    a.seg_start = img.seg_start;
+    a.seg_len = img.seg_len;
+    a.seg_page0 = img.seg_page0;
+    a.ctx_len = img.ctx_len;
+    a.counters = (int32_t*)ws_base;
+    a.pool_ctr = a.counters + (int64_t)h.n_seqs * ctx->cfg.n_kv_heads;
+    a.pool_first = h.part_start[h.n_parts_shared + h.n_parts_private];
+    a.n_pool_items = h.n_pool_items;
+    a.ws_ml = (float4*)((char*)ws_base + ml_off);
+    a.ws_o = (char*)ws_base + o_off;
+    a.bt_stride = h.bt_stride;
+    a.n_seqs = h.n_seqs;
+    a.n_merge = (int32_t)h.merge.size();
     a.n_q_heads = ctx->cfg.n_q_heads;
     a.n_kv_heads = ctx->cfg.n_kv_heads;
     a.gqa = ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads;
     a.head_dim = ctx->cfg.head_dim;
-    a.n_parts_shared = plan->host.n_parts_shared;
-    a.n_parts_private = plan->host.n_parts_private;
-    a.max_row_tiles_shared = plan->host.max_row_tiles_shared;
+    a.n_parts_shared = h.n_parts_shared;
+    a.n_parts_private = h.n_parts_private;
+    a.max_row_tiles_shared = h.max_row_tiles_shared;
     a.scale_log2e = ctx->cfg.scale * 1.4426950408889634f;
+    a.partial_format = ctx->cfg.partial_format;
+#ifdef TAPER_WG_TRACE
+    a.trace = ctx->trace;
+#endif
     return a;
+}
+taper::StepArgs make_args(const taper_ctx* ctx, const taper_plan* plan, const void* q, const void* kv, void* out,
+                          float* lse) {
+    return make_args(ctx, plan->host, plan->img, plan->ws->base, plan->ws->ml_off, plan->ws->o_off, q, kv, out, lse);
 }
 
 int check_step(const taper_ctx* ctx, const taper_plan* plan) {
     if (!ctx || !plan) return fail(TAPER_EINVAL, "null ctx or plan");
     if (plan->ctx != ctx) return fail(TAPER_EINVAL, "plan was built on another context");
-    if (ctx->host_only || !plan->buf.dev) return fail(TAPER_EHIP, "host-only context: no device work possible");
-    if (plan->host.n_partial_rows > ctx->ws_rows || ((int64_t)plan->host.n_seqs + 1) * ctx->cfg.n_kv_heads > ctx->ws_counters)
+    if (ctx->host_only || !plan->buf.dev || !plan->ws || !plan->ws->base)
+        return fail(TAPER_EHIP, "host-only context: no device work possible");
+    if (plan->host.n_partial_rows > plan->ws->rows || counters_needed(ctx->cfg, plan->host.n_seqs) > plan->ws->counters)
         return fail(TAPER_EINVAL, "workspace smaller than the plan needs");
     return TAPER_OK;
 }
 
-int enqueue_step(const taper::StepArgs& a, hipStream_t s) {
-    HIP_TRY(taper::launch_decode(a, s));
+// A failed call may have left a launch unfinished: the next launch clears the counters first.
+int hip_failed(taper_ctx* ctx, hipError_t e, const char* what) {
+    ctx->counters_suspect = true;
+    return fail_hip(e, what);
+}
+
+int enqueue_step(taper_ctx* ctx, const taper::StepArgs& a, hipStream_t s) {
+    int st = recover_counters(ctx, s);
+    if (st != TAPER_OK) return st;
+    hipError_t e = taper::launch_decode(a, s);
+    if (e != hipSuccess) return hip_failed(ctx, e, "decode kernel launch");
     return TAPER_OK;
 }
 
@@ -291,9 +418,16 @@ int taper_create(const taper_attn_config* cfg, taper_ctx** out_ctx) {
 void taper_destroy(taper_ctx* ctx) {
     if (!ctx) return;
     if (!ctx->host_only) (void)hipDeviceSynchronize();
-    if (ctx->ws) (void)hipFree(ctx->ws);
+    for (Workspace* w : ctx->workspaces) release_workspace(w);
     for (PlanBuffers& b : ctx->free_buffers) destroy_buffers(b);
     delete ctx;
+}
+
+int taper_reserve(taper_ctx* ctx, int max_seqs, int64_t max_partial_rows) {
+    if (!ctx) return fail(TAPER_EINVAL, "null argument");
+    if (max_seqs < 0 || max_partial_rows < 0) return fail(TAPER_EINVAL, "negative size");
+    Workspace* w = nullptr;
+    return current_workspace(ctx, max_partial_rows, counters_needed(ctx->cfg, max_seqs), false, &w);
 }
 
 int taper_plan_build(taper_ctx* ctx, int n_seqs, const int32_t* block_table, int bt_row_stride,
@@ -326,34 +460,19 @@ int taper_plan_build_segments(taper_ctx* ctx, int n_seqs, const int32_t* block_t
         delete plan;
         return fail(st, err);
     }
-    if (ctx->host_only) {
+    const taper::HostPlan& h = plan->host;
+    if (ctx->host_only) {  // bookkeeping only: which workspace the plan would be bound to
+        st = current_workspace(ctx, h.n_partial_rows, counters_needed(ctx->cfg, h.n_seqs), true, &plan->ws);
+        if (st != TAPER_OK) {
+            delete plan;
+            return st;
+        }
+        plan->ws->refs++;
         *out_plan = plan;
         return TAPER_OK;
     }
-    const taper::HostPlan& h = plan->host;
-    // one image: bt | items | part_start | merge_start | merge | prefix_len | seg_start | ctx_len | seg_len | seg_page0
-    struct Piece {
-        const void* src;
-        size_t bytes;
-        size_t off;
-    };
-    std::vector<Piece> pieces = {
-        {h.block_table.data(), h.block_table.size() * sizeof(int32_t), 0},
-        {h.items.data(), h.items.size() * sizeof(taper_work_item), 0},
-        {h.part_start.data(), h.part_start.size() * sizeof(int32_t), 0},
-        {h.merge_start.data(), h.merge_start.size() * sizeof(int32_t), 0},
-        {h.merge.data(), h.merge.size() * sizeof(taper_merge_entry), 0},
-        {h.prefix_len.data(), h.prefix_len.size() * sizeof(int32_t), 0},
-        {h.seg_start.data(), h.seg_start.size() * sizeof(int32_t), 0},
-        {h.ctx_len.data(), h.ctx_len.size() * sizeof(int32_t), 0},
-        {h.seg_len.data(), h.seg_len.size() * sizeof(int32_t), 0},
-        {h.seg_page0.data(), h.seg_page0.size() * sizeof(int32_t), 0},
-    };
-    size_t total = 0;
-    for (Piece& p : pieces) {
-        p.off = total;
-        total += align_up(std::max<size_t>(p.bytes, 16), 256);
-    }
+    ImagePiece pieces[10];
+    const size_t total = layout_image(h, pieces);
     hipError_t e = hipSetDevice(ctx->cfg.device);
     if (e != hipSuccess) {
         delete plan;
@@ -364,7 +483,7 @@ int taper_plan_build_segments(taper_ctx* ctx, int n_seqs, const int32_t* block_t
         delete plan;
         return st;
     }
-    for (const Piece& p : pieces) std::memcpy((char*)plan->buf.staging + p.off, p.src, p.bytes);
+    write_image(pieces, plan->buf.staging);
     hipStream_t s = (hipStream_t)hip_stream;
     e = hipMemcpyAsync(plan->buf.dev, plan->buf.staging, total, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipEventRecord(plan->buf.uploaded, s);
@@ -373,18 +492,12 @@ int taper_plan_build_segments(taper_ctx* ctx, int n_seqs, const int32_t* block_t
         taper_plan_free(plan);
         return fail(TAPER_EHIP, msg);
     }
-    char* d = (char*)plan->buf.dev;
-    plan->d_bt = (const int32_t*)(d + pieces[0].off);
-    plan->d_items = (const taper_work_item*)(d + pieces[1].off);
-    plan->d_part_start = (const int32_t*)(d + pieces[2].off);
-    plan->d_merge_start = (const int32_t*)(d + pieces[3].off);
-    plan->d_merge = (const taper_merge_entry*)(d + pieces[4].off);
-    plan->d_prefix_len = (const int32_t*)(d + pieces[5].off);
-    plan->d_seg_start = (const int32_t*)(d + pieces[6].off);
-    plan->d_ctx_len = (const int32_t*)(d + pieces[7].off);
-    plan->d_seg_len = (const int32_t*)(d + pieces[8].off);
-    plan->d_seg_page0 = (const int32_t*)(d + pieces[9].off);
-    st = ensure_workspace(ctx, h.n_partial_rows, ((int64_t)h.n_seqs + 1) * ctx->cfg.n_kv_heads);
+    plan->img = bind_image(pieces, plan->buf.dev);
+    st = current_workspace(ctx, h.n_partial_rows, counters_needed(ctx->cfg, h.n_seqs), true, &plan->ws);
+    if (st == TAPER_OK) {
+        plan->ws->refs++;
+        st = recover_counters(ctx, s);
+    }
     if (st != TAPER_OK) {
         std::string keep = g_last_error;
         taper_plan_free(plan);
@@ -400,6 +513,9 @@ void taper_plan_free(taper_plan* plan) {
     // valid: a later plan's upload into the same memory is ordered behind it on the
     // stream (one stream per context).
     if (plan->buf.dev) plan->ctx->free_buffers.push_back(plan->buf);
+    // The workspace stays (launches of this plan may still be running); one that has been superseded
+    // and has no plan left is released at the context's next growth or destruction.
+    if (plan->ws) plan->ws->refs--;
     delete plan;
 }
 
@@ -427,6 +543,8 @@ int taper_plan_export(const taper_plan* plan, taper_plan_view* v) {
     v->n_partial_rows = h.n_partial_rows;
     v->tokens_unique = h.tokens_unique;
     v->tokens_logical = h.tokens_logical;
+    v->workspace_id = plan->ws ? plan->ws->id : 0;
+    v->workspace_rows = plan->ws ? plan->ws->rows : 0;
     return TAPER_OK;
 }
 
@@ -451,7 +569,7 @@ int taper_decode_step_attention(taper_ctx* ctx, const taper_plan* plan, const vo
     int st = check_step(ctx, plan);
     if (st != TAPER_OK) return st;
     if (!q || !kv_pages || !out) return fail(TAPER_EINVAL, "null tensor pointer");
-    return enqueue_step(make_args(ctx, plan, q, kv_pages, out, lse), (hipStream_t)hip_stream);
+    return enqueue_step(ctx, make_args(ctx, plan, q, kv_pages, out, lse), (hipStream_t)hip_stream);
 }
 
 int taper_decode_step_attention_simple(taper_ctx* ctx, int n_seqs, const void* q, const void* kv_pages,
@@ -465,7 +583,7 @@ int taper_decode_step_attention_simple(taper_ctx* ctx, int n_seqs, const void* q
     st = taper_decode_step_attention(ctx, plan, q, kv_pages, out, nullptr, hip_stream);
     if (st == TAPER_OK) {
         hipError_t e = hipStreamSynchronize((hipStream_t)hip_stream);
-        if (e != hipSuccess) st = fail_hip(e, "hipStreamSynchronize");
+        if (e != hipSuccess) st = hip_failed(ctx, e, "hipStreamSynchronize");
     }
     taper_plan_free(plan);
     return st;
@@ -488,12 +606,12 @@ int taper_step_latency_probe(taper_ctx* ctx, const taper_plan* plan, int n_layer
         const int k = i - warmup;
         if (k >= 0 && hipEventRecord(ev[2 * k], s) != hipSuccess) rc = fail(TAPER_EHIP, "hipEventRecord");
         for (int l = 0; l < n_layers && rc == TAPER_OK; ++l)
-            rc = enqueue_step(make_args(ctx, plan, q_per_layer[l], kv_per_layer[l], out_per_layer[l], nullptr), s);
+            rc = enqueue_step(ctx, make_args(ctx, plan, q_per_layer[l], kv_per_layer[l], out_per_layer[l], nullptr), s);
         if (k >= 0 && rc == TAPER_OK && hipEventRecord(ev[2 * k + 1], s) != hipSuccess)
             rc = fail(TAPER_EHIP, "hipEventRecord");
     }
     hipError_t es = hipStreamSynchronize(s);
-    if (rc == TAPER_OK && es != hipSuccess) rc = fail_hip(es, "hipStreamSynchronize");
+    if (rc == TAPER_OK && es != hipSuccess) rc = hip_failed(ctx, es, "hipStreamSynchronize");
     std::vector<double> us;
     if (rc == TAPER_OK) {
         for (int k = 0; k < iters; ++k) {
@@ -551,10 +669,10 @@ int taper_kernel_times_layers(taper_ctx* ctx, const taper_plan* plan, int n_laye
         if (k >= 0) e = hipEventRecord(ev[2 * k], s);
         if (e == hipSuccess) e = taper::launch_decode(a, s);
         if (k >= 0 && e == hipSuccess) e = hipEventRecord(ev[2 * k + 1], s);
-        if (e != hipSuccess) rc = fail_hip(e, "kernel timing enqueue");
+        if (e != hipSuccess) rc = hip_failed(ctx, e, "kernel timing enqueue");
     }
     hipError_t es = hipStreamSynchronize(s);
-    if (rc == TAPER_OK && es != hipSuccess) rc = fail_hip(es, "hipStreamSynchronize");
+    if (rc == TAPER_OK && es != hipSuccess) rc = hip_failed(ctx, es, "hipStreamSynchronize");
     double sum = 0, mn = 1e300;
     if (rc == TAPER_OK) {
         for (int k = 0; k < iters; ++k) {

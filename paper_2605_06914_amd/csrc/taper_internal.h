@@ -24,8 +24,9 @@ struct StepArgs {
     const int32_t* seg_len;        // tokens of each private segment
     const int32_t* seg_page0;      // block-table entry each private segment starts at
     const int32_t* ctx_len;
-    float2* ws_ml;             // [n_partial_rows] (running max in log2 units, sum)
-    uint16_t* ws_o;            // [n_partial_rows][D] half precision, each row divided by its own sum
+    float4* ws_ml;             // [n_partial_rows] (running max in log2 units, sum, row scale, unused)
+    void* ws_o;                // [n_partial_rows][D] partial rows, each divided by its own sum: fp32, or half
+                               // precision times the row's power-of-two scale (taper_partial_format)
     int32_t* counters;         // [n_seqs][n_kv_heads] partials delivered so far; zero between launches
     int32_t* pool_ctr;         // [n_kv_heads] pool items taken so far; zero between launches
     int32_t pool_first, n_pool_items;  // the pool: items [pool_first, pool_first + n_pool_items)
@@ -36,7 +37,12 @@ struct StepArgs {
     int32_t n_parts_shared, n_parts_private;
     int32_t max_row_tiles_shared;
     float scale_log2e;         // scale * log2(e)
+    int32_t partial_format;    // taper_partial_format of ws_o
+#ifdef TAPER_WG_TRACE
+    long long* trace;          // [4 * workgroups] clocks of a trace build (see wg_trace.py), or null
+#endif
 };
+
 
 hipError_t launch_decode(const StepArgs& a, hipStream_t s);
 hipError_t launch_kv_append(const void* k_new, const void* v_new, const int64_t* slot, void* kv, int n_seqs, int n_kv_heads,

@@ -16,8 +16,9 @@
 //
 // Softmax state per query row (one lane column): running max m in log2 units
 // (scale*log2(e) folded in), running sum l, unnormalised O.  Partials of the KV
-// chunks of a sequence (m, l in fp32; O / l in half precision) are combined through
-// their (m, l) by the workgroup that delivers the sequence's last partial (merge_rows).
+// chunks of a sequence (m, l in fp32; O / l in fp32 or, by default, in half precision with a
+// per-row power-of-two scale) are combined through their (m, l) by the workgroup that delivers
+// the sequence's last partial (merge_rows).
 #include "taper_internal.h"
 
 namespace taper {
@@ -96,18 +97,75 @@ DEV float2 coherent_load2(const float* p) {
     return make_float2(__uint_as_float((unsigned)v), __uint_as_float((unsigned)(v >> 32)));
 }
 // The accumulator part of a partial row travels normalised (divided by the row's own sum, so that
-// it is a weighted mean of V rows and cannot leave the half-precision range unless V itself does)
-// and in half precision: four values per 8-byte access, half the workspace traffic, and 11 bits
-// of mantissa beside the 8 that the bf16 result keeps.
+// it is a weighted mean of V rows), in one of two formats (taper_partial_format):
+//   PF_F32   fp32, two 8-byte accesses per four values;
+//   PF_F16S  half precision after division by a power of two that brings the row's largest
+//            magnitude into [0.5, 1): one 8-byte access per four values, 11 bits of mantissa
+//            relative to the row's largest element beside the 8 the bf16 result keeps, and no
+//            limit on the magnitude of V.  The power of two sits beside (m, l) in the row's
+//            statistics record and is multiplied back in by the merge.
+constexpr int PF_F16S = TAPER_PARTIAL_F16_SCALED, PF_F32 = TAPER_PARTIAL_F32;
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-DEV void partial_store4(uint16_t* p, f32x4 v) {
-    const f16x4 h = __builtin_convertvector(v, f16x4);
-    __hip_atomic_store((unsigned long long*)p, __builtin_bit_cast(unsigned long long, h), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+template <int PF>
+struct PartialRaw {
+    unsigned long long w[PF == PF_F32 ? 2 : 1];
+};
+template <int PF>
+DEV void partial_store4(void* rows, int64_t elem, f32x4 v) {
+    if constexpr (PF == PF_F32) {
+        float* p = (float*)rows + elem;
+        coherent_store2(p, v[0], v[1]);
+        coherent_store2(p + 2, v[2], v[3]);
+    } else {
+        const f16x4 h = __builtin_convertvector(v, f16x4);
+        __hip_atomic_store((unsigned long long*)((uint16_t*)rows + elem), __builtin_bit_cast(unsigned long long, h),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
-DEV unsigned long long partial_load4_raw(const uint16_t* p) {
-    return __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// (the reader addresses a row by a 32-bit element offset from the workspace's base, which is the same for every
+// lane and stays in scalar registers: one address register per row instead of two per load.  The plan
+// keeps the partial rows of a step below 2^31 bytes.)
+template <int PF>
+DEV PartialRaw<PF> partial_load4_raw(const void* rows, int elem) {
+    PartialRaw<PF> r;
+    if constexpr (PF == PF_F32) {
+        const unsigned long long* p = (const unsigned long long*)((const char*)rows + elem * 4);
+        r.w[0] = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        r.w[1] = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        r.w[0] = __hip_atomic_load((const unsigned long long*)((const char*)rows + elem * 2), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return r;
 }
-DEV f32x4 partial_unpack4(unsigned long long raw) { return __builtin_convertvector(__builtin_bit_cast(f16x4, raw), f32x4); }
+template <int PF>
+DEV f32x4 partial_unpack4(const PartialRaw<PF>& r) {
+    if constexpr (PF == PF_F32) {
+        f32x4 v;
+        v[0] = __uint_as_float((unsigned)r.w[0]);
+        v[1] = __uint_as_float((unsigned)(r.w[0] >> 32));
+        v[2] = __uint_as_float((unsigned)r.w[1]);
+        v[3] = __uint_as_float((unsigned)(r.w[1] >> 32));
+        return v;
+    } else {
+        return __builtin_convertvector(__builtin_bit_cast(f16x4, r.w[0]), f32x4);
+    }
+}
+// The power of two 2^e that brings a row whose largest magnitude is `maxabs` into [0.5, 1), as
+// (2^e, 2^-e); e is kept inside [-126, 126] so that both are normal numbers (an all-zero row, or one
+// that holds Inf, is multiplied by some power of two all the same: it stays what it is).
+DEV float2 row_scale(float maxabs) {
+    int e = (int)((__float_as_uint(maxabs) >> 23) & 0xff) - 126;
+    e = e < -126 ? -126 : (e > 126 ? 126 : e);
+    return make_float2(__uint_as_float((unsigned)(127 + e) << 23), __uint_as_float((unsigned)(127 - e) << 23));
+}
+DEV float maxabs4(f32x4 v) { return fmaxf(fmaxf(fabsf(v[0]), fabsf(v[1])), fmaxf(fabsf(v[2]), fabsf(v[3]))); }
+// Statistics record of a partial row: (running max in log2 units, sum) and, for PF_F16S, (row scale, unused).
+template <int PF>
+DEV void stats_store(float4* rec, float m, float l, float scale) {
+    coherent_store2((float*)rec, m, l);
+    if constexpr (PF == PF_F16S) coherent_store2((float*)rec + 2, scale, 0.f);
+}
 // Every earlier vector memory operation of this wave has completed, in particular its
 // write-through stores of partial rows.  (A workgroup-scope release fence does not wait for
 // global stores on this target, and nothing weaker than a full wait orders the stores
@@ -186,9 +244,11 @@ DEV taper_merge_entry merge_entry(const StepArgs& a, const MergeMeta& mm, const 
 // does not depend on which workgroup happens to run this.  The loads bypass the caches
 // and cost a full memory latency per round, so a round keeps R entries in flight.
 //
-// Thread idx (of n_thr) owns float4 columns c, c + LPR, ... (U of them) of one row, where
-// LPR = D/4/U lanes cover a row; n_thr / LPR rows are merged per pass.
-template <int D, int U, int R>
+// A group of n_thr consecutive lanes (a workgroup, a wave or half a wave) merges one sequence;
+// groups of one wave may work on different sequences side by side.  Lane idx of the group owns
+// float4 columns c, c + LPR, ... (U of them) of one row, where LPR = D/4/U lanes cover a row;
+// n_thr / LPR rows are merged per pass.
+template <int D, int U, int R, int PF>
 DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const int hk, const int e0, const int e1,
                     const int idx_, const int n_thr) {
     constexpr int LPR = D / 4 / U;
@@ -204,26 +264,22 @@ DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const i
         for (int u = 0; u < U; ++u) acc[u] = (f32x4)(0.f);
         for (int e = e0; e < e1; e += R) {
             float2 ml[R];
-            unsigned long long o[R][U];  // four half-precision values each, unpacked when they are used
+            float sc[R];
+            PartialRaw<PF> o[R][U];  // unpacked when they are used
 #pragma unroll
             for (int k = 0; k < R; ++k) {
-                ml[k] = make_float2(-INFINITY, 0.f);
+                // (past the sequence's last entry: that entry once more, with weight zero -- no branch, and the
+                // loads of a round are issued back to back)
+                const bool real = e + k < e1;
+                const taper_merge_entry me = merge_entry(a, mm, real ? e + k : e1 - 1);
+                const int row = me.first_row + hk * me.rows_per_head + (okr ? j : 0);
+                const float* rec = (const float*)((const char*)a.ws_ml + row * 16);
+                const float2 v = coherent_load2(rec);
+                ml[k] = real && okr ? v : make_float2(-INFINITY, 0.f);
+                sc[k] = 1.f;
+                if constexpr (PF == PF_F16S) sc[k] = coherent_load2(rec + 2).x;
 #pragma unroll
-                for (int u = 0; u < U; ++u) o[k][u] = 0ull;
-                if (e + k < e1) {
-                    // the entry is the same for every lane: its rows' base address goes into scalar
-                    // registers and each load needs only a 32-bit per-lane offset
-                    const taper_merge_entry me = merge_entry(a, mm, e + k);
-                    const int64_t row0 = (int64_t)__builtin_amdgcn_readfirstlane(me.first_row) +
-                                         (int64_t)hk * __builtin_amdgcn_readfirstlane(me.rows_per_head);
-                    const uint16_t* op = a.ws_o + row0 * D;
-                    const float2* mp = a.ws_ml + row0;
-                    const unsigned jo = okr ? j : 0;
-                    const float2 v = coherent_load2((const float*)(mp + jo));
-                    if (okr) ml[k] = v;
-#pragma unroll
-                    for (int u = 0; u < U; ++u) o[k][u] = partial_load4_raw(op + (jo * D + 4u * (c0 + LPR * u)));
-                }
+                for (int u = 0; u < U; ++u) o[k][u] = partial_load4_raw<PF>(a.ws_o, row * D + 4 * (c0 + LPR * u));
             }
             float mn = M;
 #pragma unroll
@@ -236,8 +292,9 @@ DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const i
             for (int k = 0; k < R; ++k) {
                 const float w = fast_exp2(ml[k].x - mn) * ml[k].y;  // (the row was stored divided by its sum)
                 L += w;
+                const float ws = PF == PF_F16S ? w * sc[k] : w;
 #pragma unroll
-                for (int u = 0; u < U; ++u) acc[u] += w * partial_unpack4(o[k][u]);
+                for (int u = 0; u < U; ++u) acc[u] += ws * partial_unpack4<PF>(o[k][u]);
             }
             M = mn;
         }
@@ -249,9 +306,7 @@ DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const i
                 const f32x4 r = acc[u] * inv;
                 *(bf16x4*)((__bf16*)a.out + ((int64_t)s * a.n_q_heads + h) * D + 4 * (c0 + LPR * u)) = __builtin_convertvector(r, bf16x4);
             }
-#ifndef TAPER_WG_TRACE  // (trace builds use the lse buffer for their clocks)
             if (a.lse && c0 == 0) a.lse[(int64_t)s * a.n_q_heads + h] = (M + __log2f(L)) * 0.6931471805599453f;
-#endif
         }
     }
 }
@@ -259,12 +314,46 @@ DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const i
 // A workgroup that has written a partial of (sequence s, kv head hk), one of n_entries,
 // announces it.  Returns true to the one caller that arrives last: every other partial of
 // that (s, hk) has then been written through (each writer waited for its stores before
-// its increment) and the caller must merge.  The counter is left at zero for the next launch.
+// its increment) and the caller must merge.  The counter is left at zero for the next launch
+// (by a device-scope store, like every other access to it).
 DEV bool arrive_last(const StepArgs& a, const int s, const int hk, const int n_entries) {
     int* c = a.counters + (int64_t)s * a.n_kv_heads + hk;
     const bool last = atomicAdd(c, 1) == n_entries - 1;
-    if (last) *c = 0;
+    if (last) __hip_atomic_store(c, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return last;
+}
+
+// End of a shared-prefix item: every branch announces the item's partial; the branches whose set
+// is now complete are merged side by side, a wave each for up to four of them, else half a wave.
+// (One after the other they cost two to three memory round trips each, at the very end of a
+// launch's longest workgroups.)  Called by all threads after the partial rows have been stored
+// and waited for; `todo` and `n_todo` are workgroup-shared.
+template <int D, int PF>
+DEV void arrive_and_merge(const StepArgs& a, const MergeMeta& mm, int* todo, int* n_todo, const taper_work_item& item,
+                          const int hk, const int tid) {
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (wave == 0) {  // (an item has at most 64 branches)
+        const bool mine = lane < item.n_branch && arrive_last(a, item.seq0 + lane, hk, mm.ms[lane + 1] - mm.ms[lane]);
+        const unsigned long long mask = __ballot(mine);
+        if (mine) todo[__popcll(mask & ((1ull << lane) - 1))] = lane;
+        if (lane == 0) *n_todo = __popcll(mask);
+    }
+    __syncthreads();
+    const int n = *n_todo;
+    // entries in flight per round: as many as leave the launch free of register spills (the streaming loops
+    // of the callers are at the limit of the register file, and any scratch use costs microseconds per launch)
+    constexpr int R64 = PF == PF_F32 ? 6 : 8, R32 = PF == PF_F32 ? 2 : 4;
+    if (n <= 4) {
+        if (wave < n) {
+            const int b = todo[wave];
+            merge_rows<D, D / 32, R64, PF>(a, mm, item.seq0 + b, hk, mm.ms[b], mm.ms[b + 1], lane, 64);
+        }
+    } else {
+        for (int i = tid >> 5; i < n; i += 8) {
+            const int b = todo[i];
+            merge_rows<D, D / 16, R32, PF>(a, mm, item.seq0 + b, hk, mm.ms[b], mm.ms[b + 1], tid & 31, 32);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -292,7 +381,7 @@ struct PrivateSmem {
 // SOLO: the item is run by the calling wave alone (short sequences that are a single item:
 // four of them proceed side by side in a workgroup, with no barrier and no LDS); otherwise the
 // four waves of the workgroup share the item's blocks.
-template <int D, bool SOLO>
+template <int D, bool SOLO, int PF>
 DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem<D>& sm) {
     constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D;
     auto& sm_o = sm.o;
@@ -386,9 +475,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
                 __bf16* orow = (__bf16*)a.out + ((int64_t)item.seq0 * a.n_q_heads + h) * D;
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) *(bf16x4*)(orow + 16 * dt + 4 * qd) = __builtin_convertvector(O[dt] * inv, bf16x4);
-#ifndef TAPER_WG_TRACE
                 if (a.lse && qd == 0) a.lse[(int64_t)item.seq0 * a.n_q_heads + h] = (m + __log2f(l)) * 0.6931471805599453f;
-#endif
             }
             return;
         }
@@ -422,14 +509,21 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
                 const int h = hk * g + r;
                 const f32x4 res = acc * (1.0f / L);
                 *(bf16x4*)((__bf16*)a.out + ((int64_t)item.seq0 * a.n_q_heads + h) * D + 4 * d4) = __builtin_convertvector(res, bf16x4);
-#ifndef TAPER_WG_TRACE
                 if (a.lse && d4 == 0) a.lse[(int64_t)item.seq0 * a.n_q_heads + h] = (M + __log2f(L)) * 0.6931471805599453f;
-#endif
                 continue;
             }
             const int64_t slot = (int64_t)item.part_base + hk * g + r;
-            partial_store4(a.ws_o + slot * D + 4 * d4, acc * (1.0f / L));
-            if (d4 == 0) coherent_store2((float*)(a.ws_ml + slot), M, L);
+            f32x4 row = acc * (1.0f / L);
+            float2 sc = make_float2(1.f, 1.f);
+            if constexpr (PF == PF_F16S) {  // the row's D/4 lanes are neighbours inside one wave, all of them in this loop
+                float mx = maxabs4(row);
+#pragma unroll
+                for (int o = 1; o < D / 4; o *= 2) mx = fmaxf(mx, __shfl_xor(mx, o));
+                sc = row_scale(mx);
+                row *= sc.y;
+            }
+            partial_store4<PF>(a.ws_o, slot * D + 4 * d4, row);
+            if (d4 == 0) stats_store<PF>(a.ws_ml + slot, M, L, sc.x);
         }
         if (sole) {
             __syncthreads();  // the combine buffers are free for the next item
@@ -443,11 +537,9 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
 #ifdef TAPER_WG_TRACE
         const long long t_m0 = wall_clock64();
 #endif
-        if (sm.last) merge_rows<D, 1, 8>(a, sm.meta, item.seq0, hk, sm.meta.ms[0], sm.meta.ms[1], threadIdx.x, 256);
+        if (sm.last) merge_rows<D, 1, 8, PF>(a, sm.meta, item.seq0, hk, sm.meta.ms[0], sm.meta.ms[1], threadIdx.x, 256);
 #ifdef TAPER_WG_TRACE
-        if (threadIdx.x == 0 && a.lse) {
-            ((long long*)a.lse)[4 * blockIdx.x + 3] += wall_clock64() - t_m0;
-        }
+        if (threadIdx.x == 0 && a.trace) a.trace[4 * blockIdx.x + 3] += wall_clock64() - t_m0;
 #endif
     }
 }
@@ -456,7 +548,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
 // can take from its kv head's pool.  Every workgroup makes exactly one claim past the end of
 // the pool; the one that makes the last of those puts the counter back to zero for the next
 // launch.
-template <int D>
+template <int D, int PF>
 DEV void private_items(const StepArgs& a, int it0, const int it1, const int hk, PrivateSmem<D>& sm) {
     const int wgs_per_head = a.n_parts_shared + a.n_parts_private;  // = gridDim.x / n_kv_heads
     for (;;) {
@@ -470,7 +562,8 @@ DEV void private_items(const StepArgs& a, int it0, const int it1, const int hk, 
             const int i = sm.pick;
             __syncthreads();
             if (i >= a.n_pool_items) {
-                if (threadIdx.x == 0 && i == a.n_pool_items + wgs_per_head - 1) a.pool_ctr[hk] = 0;
+                if (threadIdx.x == 0 && i == a.n_pool_items + wgs_per_head - 1)
+                    __hip_atomic_store(a.pool_ctr + hk, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 return;
             }
             it = a.pool_first + i;
@@ -479,12 +572,12 @@ DEV void private_items(const StepArgs& a, int it0, const int it1, const int hk, 
             int end = it + 1;
             while (end < it1 && a.items[end].kind == 3) ++end;
             const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-            for (int k = it + wave; k < end; k += 4) private_item<D, true>(a, k, hk, sm);
+            for (int k = it + wave; k < end; k += 4) private_item<D, true, PF>(a, k, hk, sm);
             it0 = end;
             __syncthreads();
             continue;
         }
-        private_item<D, false>(a, it, hk, sm);
+        private_item<D, false, PF>(a, it, hk, sm);
     }
 }
 
@@ -502,11 +595,48 @@ struct SharedSmem {
     static constexpr int PAGE_LDS = TILE + 4 * VQ;
     static constexpr int BUF = 4 * PAGE_LDS;  // 4 pages = 64 tokens
     __bf16 kv[2 * BUF];
-    int last[64];  // per branch of the current item
+    int todo[64];  // branches of the current item whose partials are complete
+    int n_todo;
     MergeMeta meta;
 };
 
-template <int D, int NTW>
+// The partial rows of a shared-prefix item: tile k of this wave holds row 16 * (wave + 4k) + n of the
+// item's R rows in lane column n, 4 values per 16-dim group and lane group.
+template <int D, int NTW, int PF>
+DEV void store_shared_partials(const StepArgs& a, const taper_work_item& item, const int hk, const int R, const int n_act,
+                               const int wave, const int n, const int qd, const float (&m)[NTW], const float (&l)[NTW],
+                               const f32x4 (&O)[NTW][D / 16]) {
+    constexpr int DT = D / 16;
+#pragma unroll
+    for (int k = 0; k < NTW; ++k) {
+        if (k < n_act) {
+            const float lt = sum_lane_groups(l[k]);
+            const float inv = 1.0f / lt;
+            float2 sc = make_float2(1.f, 1.f);
+            if constexpr (PF == PF_F16S) {  // (all 64 lanes are here: k < n_act is wave-uniform)
+                float mx = 0.f;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) mx = fmaxf(mx, maxabs4(O[k][dt]));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                sc = row_scale(mx * inv);
+            }
+            const int r = 16 * (wave + 4 * k) + n;
+            if (r < R) {
+                const int64_t slot = (int64_t)item.part_base + (int64_t)hk * R + r;
+                if (qd == 0) stats_store<PF>(a.ws_ml + slot, m[k], lt, sc.x);
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    f32x4 v = O[k][dt] * inv;
+                    if constexpr (PF == PF_F16S) v *= sc.y;
+                    partial_store4<PF>(a.ws_o, slot * D + 16 * dt + 4 * qd, v);
+                }
+            }
+        }
+    }
+}
+
+template <int D, int NTW, int PF>
 DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem<D>& sm) {
     constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D;
     constexpr int QE = SharedSmem<D>::QE, VQ = SharedSmem<D>::VQ, PAGE_LDS = SharedSmem<D>::PAGE_LDS,
@@ -594,24 +724,41 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
                 if (nv <= 0) break;
                 const __bf16* pa = lds + buf * BUF + (2 * hf) * PAGE_LDS;
                 const __bf16* pb = pa + PAGE_LDS;
-                bf16x8 kx[KS], ky[KS];
-#pragma unroll
-                for (int j = 0; j < KS; ++j) {
-                    kx[j] = *(const bf16x8*)(pa + koff + j * 512);
-                    ky[j] = *(const bf16x8*)(pb + koff + j * 512);
-                }
                 bf16x8 pf[NTW];
+                if constexpr (NTW == 1) {
+                    // one tile per wave: every K fragment is used once, so the two pages' fragments take turns
+                    // in one set of registers (this variant has none to spare beside its three staging sets)
+                    f32x4 sx = (f32x4)(0.f), sy = (f32x4)(0.f);
+                    bf16x8 kf[KS];
 #pragma unroll
-                for (int k = 0; k < NTW; ++k) {
-                    if (k < n_act) {
-                        f32x4 sx = (f32x4)(0.f), sy = (f32x4)(0.f);
+                    for (int j = 0; j < KS; ++j) kf[j] = *(const bf16x8*)(pa + koff + j * 512);
 #pragma unroll
-                        for (int j = 0; j < KS; ++j) {
-                            sx = mfma16(kx[j], qf[k][j], sx);
-                            sy = mfma16(ky[j], qf[k][j], sy);
+                    for (int j = 0; j < KS; ++j) sx = mfma16(kf[j], qf[0][j], sx);
+#pragma unroll
+                    for (int j = 0; j < KS; ++j) kf[j] = *(const bf16x8*)(pb + koff + j * 512);
+#pragma unroll
+                    for (int j = 0; j < KS; ++j) sy = mfma16(kf[j], qf[0][j], sy);
+                    if (nv < 32) mask_tail(sx, sy, qd, nv);
+                    pf[0] = softmax_block<DT>(sx, sy, c, m[0], l[0], O[0]);
+                } else {
+                    bf16x8 kx[KS], ky[KS];
+#pragma unroll
+                    for (int j = 0; j < KS; ++j) {
+                        kx[j] = *(const bf16x8*)(pa + koff + j * 512);
+                        ky[j] = *(const bf16x8*)(pb + koff + j * 512);
+                    }
+#pragma unroll
+                    for (int k = 0; k < NTW; ++k) {
+                        if (k < n_act) {
+                            f32x4 sx = (f32x4)(0.f), sy = (f32x4)(0.f);
+#pragma unroll
+                            for (int j = 0; j < KS; ++j) {
+                                sx = mfma16(kx[j], qf[k][j], sx);
+                                sy = mfma16(ky[j], qf[k][j], sy);
+                            }
+                            if (nv < 32) mask_tail(sx, sy, qd, nv);
+                            pf[k] = softmax_block<DT>(sx, sy, c, m[k], l[k], O[k]);
                         }
-                        if (nv < 32) mask_tail(sx, sy, qd, nv);
-                        pf[k] = softmax_block<DT>(sx, sy, c, m[k], l[k], O[k]);
                     }
                 }
                 // (four V fragment pairs at a time, then one branch for the ragged tail: a branch per
@@ -680,33 +827,19 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
             }
         }
 
-#pragma unroll
-        for (int k = 0; k < NTW; ++k) {
-            if (k < n_act) {
-                const float lt = sum_lane_groups(l[k]);
-                const int r = 16 * (wave + 4 * k) + n;
-                if (r < R) {
-                    const int64_t slot = (int64_t)item.part_base + (int64_t)hk * R + r;
-                    if (qd == 0) coherent_store2((float*)(a.ws_ml + slot), m[k], lt);
-                    const float inv = 1.0f / lt;
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) partial_store4(a.ws_o + slot * D + 16 * dt + 4 * qd, O[k][dt] * inv);
-                }
-            }
-        }
-        // publish the partials; for every branch whose set is now complete, merge (one wave per branch)
+        // (lane coordinates are derived afresh: shared with the ones above, they would stay live through the streaming loop)
+        const int tid_e = opaque(threadIdx.x);
+        store_shared_partials<D, NTW, PF>(a, item, hk, R, n_act, wave, tid_e & 15, (tid_e & 63) >> 4, m, l, O);
+        // publish the partials; merge every branch whose set is now complete
         stores_done();
-        __syncthreads();
-        if (tid < item.n_branch) sm.last[tid] = arrive_last(a, item.seq0 + tid, hk, sm.meta.ms[tid + 1] - sm.meta.ms[tid]);
         __syncthreads();
 #ifdef TAPER_WG_TRACE
         const long long t_m0 = wall_clock64();
 #endif
-        for (int b = wave; b < item.n_branch; b += 4)
-            if (sm.last[b]) merge_rows<D, D / 32, (NTW == 1 ? 6 : 8)>(a, sm.meta, item.seq0 + b, hk, sm.meta.ms[b], sm.meta.ms[b + 1], lane, 64);
+        arrive_and_merge<D, PF>(a, sm.meta, sm.todo, &sm.n_todo, item, hk, tid_e);
 #ifdef TAPER_WG_TRACE
         __syncthreads();
-        if (tid == 0 && a.lse) ((long long*)a.lse)[4 * blockIdx.x + 3] += wall_clock64() - t_m0;
+        if (tid == 0 && a.trace) a.trace[4 * blockIdx.x + 3] += wall_clock64() - t_m0;
 #endif
         __syncthreads();
     }
@@ -771,7 +904,7 @@ DEV void lds_read_v(unsigned addr, bf16x4 (&va)[4], bf16x4 (&vb)[4]) {
         : "v"(addr), "n"(PB), "n"(PB + 128), "n"(PB + 256), "n"(PB + 384));
 }
 
-template <int D>
+template <int D, int PF>
 DEV void shared_path_wide(const StepArgs& a, const int part, const int hk, SharedSmem<D>& sm) {
     static_assert(D == 128, "a wave's 64 x 16 bytes must be one quarter of a tile");
     constexpr int NTW = 3, KS = D / 32, DT = D / 16, TILE = 16 * D;
@@ -891,26 +1024,11 @@ DEV void shared_path_wide(const StepArgs& a, const int part, const int hk, Share
             fetch_ids(b + 4);  // for the next iteration's stage: its latency overlaps the wait for block b + 1
         }
 
-#pragma unroll
-        for (int k = 0; k < NTW; ++k) {
-            if (k < n_act) {
-                const float lt = sum_lane_groups(l[k]);
-                const int r = 16 * (wave + 4 * k) + n;
-                if (r < R) {
-                    const int64_t slot = (int64_t)item.part_base + (int64_t)hk * R + r;
-                    if (qd == 0) coherent_store2((float*)(a.ws_ml + slot), m[k], lt);
-                    const float inv = 1.0f / lt;
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) partial_store4(a.ws_o + slot * D + 16 * dt + 4 * qd, O[k][dt] * inv);
-                }
-            }
-        }
+        const int tid_e = opaque(threadIdx.x);
+        store_shared_partials<D, NTW, PF>(a, item, hk, R, n_act, wave, tid_e & 15, (tid_e & 63) >> 4, m, l, O);
         stores_done();
         __syncthreads();
-        if (tid < item.n_branch) sm.last[tid] = arrive_last(a, item.seq0 + tid, hk, sm.meta.ms[tid + 1] - sm.meta.ms[tid]);
-        __syncthreads();
-        for (int b = wave; b < item.n_branch; b += 4)
-            if (sm.last[b]) merge_rows<D, D / 32, 8>(a, sm.meta, item.seq0 + b, hk, sm.meta.ms[b], sm.meta.ms[b + 1], lane, 64);
+        arrive_and_merge<D, PF>(a, sm.meta, sm.todo, &sm.n_todo, item, hk, tid_e);
         __syncthreads();
     }
 }
@@ -919,7 +1037,7 @@ DEV void shared_path_wide(const StepArgs& a, const int part, const int hk, Share
 // One launch per layer: workgroup (share, kv head).  Shares below n_parts_shared
 // stream shared prefixes, the others private tokens; both kinds run side by side.
 // ---------------------------------------------------------------------------
-template <int D, int NTW>
+template <int D, int NTW, int PF>
 __global__ __launch_bounds__(256, (NTW <= 2 || D == 128 ? 2 : 1)) void decode_kernel(StepArgs a) {
     union Smem {
         SharedSmem<D> sh;
@@ -928,27 +1046,27 @@ __global__ __launch_bounds__(256, (NTW <= 2 || D == 128 ? 2 : 1)) void decode_ke
     __shared__ __attribute__((aligned(16))) char smem_raw[sizeof(Smem)];
     const int part = blockIdx.x / a.n_kv_heads;
     const int hk = blockIdx.x % a.n_kv_heads;
-#ifdef TAPER_WG_TRACE  // development builds only: per-workgroup clocks (start, shared share done, left, time in merges) into the lse buffer
-    long long* trace = (long long*)a.lse;
-    if (threadIdx.x == 0) trace[4 * blockIdx.x] = wall_clock64();
+#ifdef TAPER_WG_TRACE  // trace builds only (wg_trace.py): per-workgroup clocks -- start, shared share done, left, time in merges
+    long long* trace = a.trace;
+    if (threadIdx.x == 0 && trace) trace[4 * blockIdx.x] = wall_clock64();
 #endif
     int it0 = 0, it1 = 0;  // private items of this workgroup's share
     if (part < a.n_parts_shared) {
         if constexpr (NTW == 3 && D == 128)
-            shared_path_wide<D>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
+            shared_path_wide<D, PF>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
         else
-            shared_path<D, NTW>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
+            shared_path<D, NTW, PF>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
         __syncthreads();
     } else {
         it0 = a.part_start[part];
         it1 = a.part_start[part + 1];
     }
 #ifdef TAPER_WG_TRACE
-    if (threadIdx.x == 0) trace[4 * blockIdx.x + 1] = wall_clock64();  // shared share done / private share about to start
+    if (threadIdx.x == 0 && trace) trace[4 * blockIdx.x + 1] = wall_clock64();  // shared share done / private share about to start
 #endif
-    private_items<D>(a, it0, it1, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
+    private_items<D, PF>(a, it0, it1, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
 #ifdef TAPER_WG_TRACE
-    if (threadIdx.x == 0) trace[4 * blockIdx.x + 2] = wall_clock64();
+    if (threadIdx.x == 0 && trace) trace[4 * blockIdx.x + 2] = wall_clock64();
 #endif
 }
 
@@ -1040,25 +1158,25 @@ hipError_t launch_stream_read(const void* base, int64_t pieces_per_wg, int n_wor
     return hipGetLastError();
 }
 
+template <int D, int PF>
+static hipError_t launch_decode_as(const StepArgs& a, const dim3 grid, const int ntw, hipStream_t s) {
+    const dim3 block(256);
+    if (ntw <= 1) hipLaunchKernelGGL((decode_kernel<D, 1, PF>), grid, block, 0, s, a);
+    else if (ntw == 2) hipLaunchKernelGGL((decode_kernel<D, 2, PF>), grid, block, 0, s, a);
+    else if (ntw == 3) hipLaunchKernelGGL((decode_kernel<D, 3, PF>), grid, block, 0, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 hipError_t launch_decode(const StepArgs& a, hipStream_t s) {
     const int n_parts = a.n_parts_shared + a.n_parts_private;
     if (n_parts == 0) return hipSuccess;
-    const dim3 grid(n_parts * a.n_kv_heads), block(256);
+    const dim3 grid(n_parts * a.n_kv_heads);
     const int ntw = a.n_parts_shared ? (a.max_row_tiles_shared + 3) / 4 : 1;
-    if (a.head_dim == 128) {
-        if (ntw <= 1) hipLaunchKernelGGL((decode_kernel<128, 1>), grid, block, 0, s, a);
-        else if (ntw == 2) hipLaunchKernelGGL((decode_kernel<128, 2>), grid, block, 0, s, a);
-        else if (ntw == 3) hipLaunchKernelGGL((decode_kernel<128, 3>), grid, block, 0, s, a);
-        else return hipErrorInvalidValue;
-    } else if (a.head_dim == 64) {
-        if (ntw <= 1) hipLaunchKernelGGL((decode_kernel<64, 1>), grid, block, 0, s, a);
-        else if (ntw == 2) hipLaunchKernelGGL((decode_kernel<64, 2>), grid, block, 0, s, a);
-        else if (ntw == 3) hipLaunchKernelGGL((decode_kernel<64, 3>), grid, block, 0, s, a);
-        else return hipErrorInvalidValue;
-    } else {
-        return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    const bool f32 = a.partial_format == PF_F32;
+    if (a.head_dim == 128) return f32 ? launch_decode_as<128, PF_F32>(a, grid, ntw, s) : launch_decode_as<128, PF_F16S>(a, grid, ntw, s);
+    if (a.head_dim == 64) return f32 ? launch_decode_as<64, PF_F32>(a, grid, ntw, s) : launch_decode_as<64, PF_F16S>(a, grid, ntw, s);
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_resolve_slots(const StepArgs& a, int64_t* slots, int64_t stride, hipStream_t s) {

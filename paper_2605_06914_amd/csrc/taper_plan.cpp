@@ -41,6 +41,10 @@ int validate_config(const taper_attn_config& cfg, std::string* err) {
         *err = "scale must be positive and finite";
         return TAPER_EINVAL;
     }
+    if (cfg.partial_format != TAPER_PARTIAL_F16_SCALED && cfg.partial_format != TAPER_PARTIAL_F32) {
+        *err = "unknown partial_format";
+        return TAPER_EINVAL;
+    }
     return TAPER_OK;
 }
 
@@ -472,7 +476,8 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
     std::vector<std::vector<taper_merge_entry>> per_seq(n_seqs);
     int64_t rows = 0;
     for (taper_work_item& it : p.items) {
-        if (rows + (int64_t)it.n_branch * cfg.n_q_heads > INT32_MAX) {
+        // (the merge addresses partial rows by 32-bit byte offsets: fp32 rows of a step stay below 2^31 bytes)
+        if ((rows + (int64_t)it.n_branch * cfg.n_q_heads) * cfg.head_dim * 4 > INT32_MAX) {
             *err = "too many partial rows";
             return TAPER_EINVAL;
         }

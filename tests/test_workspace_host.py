@@ -1,0 +1,101 @@
+"""CPU-only tests of the workspace bookkeeping (host-only contexts keep the same records as
+device contexts, without the device memory): a plan stays bound to the workspace it was built
+with whatever is built later, so that launches in flight and captured graphs keep valid
+addresses; and of the build itself: the decode kernels must not use scratch memory."""
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2605_06914_amd import Context, TaperError, TAPER_EINVAL
+from paper_2605_06914_amd.build import CSRC, HIP_FLAGS, ROOT
+from taper_inputs import AttnShape, structure_config2, structure_config3, structure_custom
+
+QWEN = AttnShape(64, 8, 128, 16)
+
+
+def build(ctx, st, **kw):
+    return ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages, **kw)
+
+
+def test_a_larger_plan_gets_a_workspace_of_its_own_and_leaves_the_old_one_alone():
+    ctx = Context(64, 8, 128, device=-1)
+    small = build(ctx, structure_custom(QWEN, [(700, [0, 33, 64]), (2100, [0])], seed=1))
+    a = small.export()
+    assert a["workspace_id"] == 1 and a["workspace_rows"] >= a["n_partial_rows"]
+    big = build(ctx, structure_config3())
+    b = big.export()
+    assert b["n_partial_rows"] > a["workspace_rows"], "the second plan must not fit the first workspace"
+    assert b["workspace_id"] == 2 and b["workspace_rows"] >= b["n_partial_rows"]
+    again = small.export()  # the first plan still sits where it sat
+    assert again["workspace_id"] == 1 and again["workspace_rows"] == a["workspace_rows"]
+    # a plan that fits the current workspace shares it, also a small one
+    third = build(ctx, structure_custom(QWEN, [(50, [0, 7])], seed=2))
+    assert third.export()["workspace_id"] == 2
+    for p in (small, big, third):
+        p.free()
+    # steady state: the same batch again and again never moves
+    ids = set()
+    for _ in range(5):
+        p = build(ctx, structure_config3())
+        ids.add(p.export()["workspace_id"])
+        p.free()
+    assert ids == {2}
+    ctx.close()
+
+
+def test_reserve_sizes_the_workspace_ahead_of_time():
+    ctx = Context(64, 8, 128, device=-1)
+    probe = build(ctx, structure_config3())
+    rows = probe.export()["n_partial_rows"]
+    probe.free()
+    ctx2 = Context(64, 8, 128, device=-1)
+    ctx2.reserve(max_seqs=128, max_partial_rows=rows)
+    p = build(ctx2, structure_config3())
+    e = p.export()
+    assert e["workspace_id"] == 1 and e["workspace_rows"] >= rows
+    q = build(ctx2, structure_config2())
+    assert q.export()["workspace_id"] == 1
+    p.free()
+    q.free()
+    ctx2.reserve(max_seqs=1, max_partial_rows=1)  # smaller than what is there: nothing happens
+    r = build(ctx2, structure_config3())
+    assert r.export()["workspace_id"] == 1
+    r.free()
+    with pytest.raises(TaperError) as err:
+        ctx2.reserve(-1, 5)
+    assert err.value.status == TAPER_EINVAL
+    ctx.close()
+    ctx2.close()
+
+
+def test_unknown_partial_format_is_rejected():
+    with pytest.raises(TaperError) as err:
+        Context(64, 8, 128, device=-1, partial_format=7)
+    assert err.value.status == TAPER_EINVAL
+    for fmt in ("f16_scaled", "f32"):
+        Context(64, 8, 128, device=-1, partial_format=fmt).close()
+
+
+def test_decode_kernels_use_no_scratch_memory(tmp_path):
+    """Any scratch use makes every launch set up scratch for the whole grid (microseconds per launch);
+    the kernels are written to fit the register file, and a change that spills must not go unnoticed."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIP_FLAGS if f not in ("-shared",)]
+    cmd = [hipcc, *flags, "--cuda-device-only", "-c", "-Rpass-analysis=kernel-resource-usage",
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", str(tmp_path / "k.o"),
+           os.path.join(CSRC, "taper_kernels.hip")]
+    out = subprocess.run(cmd, capture_output=True, text=True, timeout=900)
+    assert out.returncode == 0, out.stderr[-2000:]
+    name, seen = None, {}
+    for line in out.stderr.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name:
+            seen[name] = int(m.group(1))
+    decode = {k: v for k, v in seen.items() if "decode_kernel" in k}
+    assert len(decode) == 12, sorted(seen)  # head_dim 64 / 128 x 1..3 row tiles per wave x 2 partial formats
+    assert all(v == 0 for v in decode.values()), {k: v for k, v in decode.items() if v}
