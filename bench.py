@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--kernel-iters", type=int, default=50)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times: scales the FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--partial-format", default="f16_scaled", choices=["f16_scaled", "f32"],
+                    help="how partial rows travel between workgroups (taper_partial_format)")
     ap.add_argument("--sweep-pools", type=int, default=16, help="distinct KV pools the 64 layers of the sweep cycle through")
     ap.add_argument("--sweep-k", default="0,2,4,8,16", help="widths of the admission sweep to run (k = 0 is always run: the base)")
     return ap.parse_args()
@@ -486,7 +488,7 @@ def main():
         outs.append(torch.zeros((st.n_seqs, sh.n_q_heads, sh.head_dim), device=dev, dtype=torch.bfloat16))
     torch.cuda.synchronize()
 
-    ctx = Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, device=0)
+    ctx = Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, device=0, partial_format=args.partial_format)
     plan_kw = dict(target_workgroups=args.target_workgroups, share_prefix=not args.no_share,
                    shared_cost_pct=args.shared_cost_pct)
 

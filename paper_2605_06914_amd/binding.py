@@ -182,6 +182,23 @@ def _ptr(t) -> int:
     return int(t) if isinstance(t, int) else int(t.data_ptr())
 
 
+def _dev(t, what: str, numel: int, dtype: str, device: int) -> int:
+    """Device pointer of tensor `t` after checking what the C ABI cannot see from a bare pointer: element
+    type, contiguity, device and size (an undersized, strided or wrong-device tensor would become an
+    out-of-bounds access inside the kernel).  A raw int is passed through: the caller vouches for it."""
+    if isinstance(t, int):
+        return t
+    if str(t.dtype).rsplit(".", 1)[-1] != dtype:
+        raise TaperError(TAPER_EINVAL, f"{what} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise TaperError(TAPER_EINVAL, f"{what} must be contiguous")
+    if t.device.type != "cuda" or (t.device.index or 0) != device:
+        raise TaperError(TAPER_EINVAL, f"{what} must live on cuda:{device}, got {t.device}")
+    if t.numel() < numel:
+        raise TaperError(TAPER_EINVAL, f"{what} holds {t.numel()} elements, the step needs {numel}")
+    return int(t.data_ptr())
+
+
 def _stream(stream) -> int:
     if stream is None:
         import torch
@@ -192,8 +209,9 @@ def _stream(stream) -> int:
 class Plan:
     """One decode step's integer metadata (taper_plan)."""
 
-    def __init__(self, ctx: "Context", handle: int):
+    def __init__(self, ctx: "Context", handle: int, n_seqs: int = 0, n_pool_pages: int = 0):
         self.ctx, self._h = ctx, handle
+        self.n_seqs, self.n_pool_pages = int(n_seqs), int(n_pool_pages)
 
     def free(self):
         # a plan hands its buffers back to its context, so it must be freed first
@@ -236,7 +254,8 @@ class Plan:
         return out
 
     def resolve_slots(self, slots_dev, stride: int, stream=None):
-        _check(load_library().taper_plan_resolve_slots(self.ctx._h, self._h, _ptr(slots_dev), stride, _stream(stream)))
+        ptr = _dev(slots_dev, "slots", self.n_seqs * int(stride), "int64", self.ctx.cfg.device)
+        _check(load_library().taper_plan_resolve_slots(self.ctx._h, self._h, ptr, stride, _stream(stream)))
 
 
 class Context:
@@ -285,7 +304,7 @@ class Context:
         _check(load_library().taper_plan_build(self._h, bt.shape[0], bt.ctypes.data, bt.shape[1], grp.ctypes.data,
                                                pl.ctypes.data, sl.ctypes.data, int(n_pool_pages), ctypes.byref(opts),
                                                st, ctypes.byref(h)))
-        return Plan(self, h.value)
+        return Plan(self, h.value, bt.shape[0], n_pool_pages)
 
     def plan_build_segments(self, block_table, branch_group, prefix_len, seg_start, seg_len, n_pool_pages: int,
                             stream=None, **options) -> Plan:
@@ -309,28 +328,54 @@ class Context:
         _check(load_library().taper_plan_build_segments(self._h, bt.shape[0], bt.ctypes.data, bt.shape[1], grp.ctypes.data,
                                                         pl.ctypes.data, ss.ctypes.data, sl.ctypes.data if len(sl) else None,
                                                         int(n_pool_pages), ctypes.byref(opts), st, ctypes.byref(h)))
-        return Plan(self, h.value)
+        return Plan(self, h.value, bt.shape[0], n_pool_pages)
 
-    def kv_append(self, k_new, v_new, slots_dev, kv_pages, n_seqs: int, stream=None):
-        _check(load_library().taper_kv_append(self._h, int(n_seqs), _ptr(k_new), _ptr(v_new), _ptr(slots_dev),
-                                              _ptr(kv_pages), _stream(stream)))
+    # elements of the tensors of a step of n_seqs sequences over a pool of n_pool_pages pages
+    def _qo_elems(self, n_seqs: int) -> int:
+        return int(n_seqs) * self.cfg.n_q_heads * self.cfg.head_dim
+
+    def _kv_row_elems(self, n_seqs: int) -> int:
+        return int(n_seqs) * self.cfg.n_kv_heads * self.cfg.head_dim
+
+    def _pool_elems(self, n_pool_pages: int) -> int:
+        return int(n_pool_pages) * 2 * self.cfg.n_kv_heads * self.cfg.page_size * self.cfg.head_dim
+
+    def _step_ptrs(self, n_seqs, n_pool_pages, q, kv_pages, out, lse=None):
+        d = self.cfg.device
+        return (_dev(q, "q", self._qo_elems(n_seqs), "bfloat16", d),
+                _dev(kv_pages, "kv_pages", self._pool_elems(n_pool_pages), "bfloat16", d),
+                _dev(out, "out", self._qo_elems(n_seqs), "bfloat16", d),
+                _dev(lse, "lse", int(n_seqs) * self.cfg.n_q_heads, "float32", d) if lse is not None else None)
+
+    def kv_append(self, k_new, v_new, slots_dev, kv_pages, n_seqs: int, stream=None, n_pool_pages: int = 0):
+        """n_pool_pages (optional): the pool's size, so that the pool tensor's size can be checked too."""
+        d = self.cfg.device
+        _check(load_library().taper_kv_append(self._h, int(n_seqs),
+                                              _dev(k_new, "k_new", self._kv_row_elems(n_seqs), "bfloat16", d),
+                                              _dev(v_new, "v_new", self._kv_row_elems(n_seqs), "bfloat16", d),
+                                              _dev(slots_dev, "slots", int(n_seqs), "int64", d),
+                                              _dev(kv_pages, "kv_pages", self._pool_elems(n_pool_pages), "bfloat16", d),
+                                              _stream(stream)))
 
     def decode_step_attention(self, plan: Plan, q, kv_pages, out, lse=None, stream=None):
-        _check(load_library().taper_decode_step_attention(self._h, plan._h, _ptr(q), _ptr(kv_pages), _ptr(out),
-                                                          _ptr(lse) if lse is not None else None, _stream(stream)))
+        pq, pkv, pout, plse = self._step_ptrs(plan.n_seqs, plan.n_pool_pages, q, kv_pages, out, lse)
+        _check(load_library().taper_decode_step_attention(self._h, plan._h, pq, pkv, pout, plse, _stream(stream)))
 
     def decode_step_attention_simple(self, q, kv_pages, n_pool_pages, block_table, branch_group, prefix_len,
                                      suffix_len, out, stream=None):
         bt = _i32(block_table)
         grp, pl, sl = _i32(branch_group), _i32(prefix_len), _i32(suffix_len)
+        pq, pkv, pout, _ = self._step_ptrs(bt.shape[0], n_pool_pages, q, kv_pages, out)
         _check(load_library().taper_decode_step_attention_simple(
-            self._h, bt.shape[0], _ptr(q), _ptr(kv_pages), int(n_pool_pages), bt.ctypes.data, bt.shape[1],
-            grp.ctypes.data, pl.ctypes.data, sl.ctypes.data, _ptr(out), _stream(stream)))
+            self._h, bt.shape[0], pq, pkv, int(n_pool_pages), bt.ctypes.data, bt.shape[1],
+            grp.ctypes.data, pl.ctypes.data, sl.ctypes.data, pout, _stream(stream)))
 
     def step_latency_probe(self, plan: Plan, q_layers: Sequence, kv_layers: Sequence, out_layers: Sequence,
                            warmup: int = 10, iters: int = 50, stream=None) -> taper_probe_result:
         n = len(q_layers)
         assert len(kv_layers) == n and len(out_layers) == n
+        for l in range(n):
+            self._step_ptrs(plan.n_seqs, plan.n_pool_pages, q_layers[l], kv_layers[l], out_layers[l])
         mk = lambda ts: (ctypes.c_void_p * n)(*[_ptr(t) for t in ts])
         res = taper_probe_result()
         _check(load_library().taper_step_latency_probe(self._h, plan._h, n, mk(q_layers), mk(kv_layers),
@@ -340,8 +385,8 @@ class Context:
 
     def kernel_times(self, plan: Plan, q, kv_pages, out, warmup: int = 5, iters: int = 20, stream=None):
         us = (ctypes.c_double * 2)()
-        _check(load_library().taper_kernel_times(self._h, plan._h, _ptr(q), _ptr(kv_pages), _ptr(out), warmup, iters,
-                                                 _stream(stream), us))
+        pq, pkv, pout, _ = self._step_ptrs(plan.n_seqs, plan.n_pool_pages, q, kv_pages, out)
+        _check(load_library().taper_kernel_times(self._h, plan._h, pq, pkv, pout, warmup, iters, _stream(stream), us))
         return dict(decode_us=us[0], decode_us_min=us[1])
 
     def kernel_times_layers(self, plan: Plan, q_layers: Sequence, kv_layers: Sequence, out_layers: Sequence,
@@ -349,6 +394,8 @@ class Context:
         """Launch i runs on layer i mod len(layers): distinct pools, so no launch reuses cached KV of an earlier one."""
         n = len(q_layers)
         assert len(kv_layers) == n and len(out_layers) == n
+        for l in range(n):
+            self._step_ptrs(plan.n_seqs, plan.n_pool_pages, q_layers[l], kv_layers[l], out_layers[l])
         mk = lambda ts: (ctypes.c_void_p * n)(*[_ptr(t) for t in ts])
         us = (ctypes.c_double * 2)()
         _check(load_library().taper_kernel_times_layers(self._h, plan._h, n, mk(q_layers), mk(kv_layers), mk(out_layers),

@@ -18,17 +18,27 @@ HIP_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
+TRACE_LIB = os.path.join(PKG, "libtaper_attn_trace.so")  # development aid: per-workgroup clocks (wg_trace.py)
+
+
+def build_library(verbose: bool = False, extra_flags=(), trace: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + f".tmp{os.getpid()}"
+    if trace:
+        return _build(hipcc, TRACE_LIB, ["-DTAPER_WG_TRACE", *extra_flags], verbose)
+    return _build(hipcc, LIB, list(extra_flags), verbose)
+
+
+def _build(hipcc, lib, extra_flags, verbose) -> str:
+    tmp = lib + f".tmp{os.getpid()}"
     cmd = [hipcc, *HIP_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-o", tmp, *[os.path.join(CSRC, s) for s in SOURCES]]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True, extra_flags=sys.argv[1:]))
+    args = sys.argv[1:]
+    print(build_library(verbose=True, extra_flags=[a for a in args if a != "--trace"], trace="--trace" in args))

@@ -12,6 +12,9 @@
 #include "taper_attn.h"
 #include "taper_internal.h"
 #include "taper_plan.h"
+#ifdef TAPER_WG_TRACE
+#include "taper_trace.h"
+#endif
 
 namespace {
 thread_local std::string g_last_error;
@@ -203,7 +206,11 @@ int current_workspace(taper_ctx* ctx, int64_t rows, int64_t counters, bool headr
         *out = cur;
         return TAPER_OK;
     }
-    // growth: the only moment anything is freed (superseded workspaces that no plan is bound to any more)
+    if (cur) {  // never smaller than what it replaces
+        rows = std::max(rows, cur->rows);
+        counters = std::max(counters, cur->counters);
+    }
+    // growth: the only moment anything is freed (workspaces, the current one included, that no plan is bound to)
     bool synced = false;
     for (size_t i = 0; i < ctx->workspaces.size();) {
         Workspace* w = ctx->workspaces[i];
@@ -220,10 +227,6 @@ int current_workspace(taper_ctx* ctx, int64_t rows, int64_t counters, bool headr
     }
     Workspace* w = new (std::nothrow) Workspace();
     if (!w) return fail(TAPER_ENOMEM, "host allocation failed");
-    if (cur) {  // never smaller than what it replaces
-        rows = std::max(rows, cur->rows);
-        counters = std::max(counters, cur->counters);
-    }
     w->rows = headroom ? rows + rows / 4 + 1024 : rows;  // head-room so that slowly growing steps do not reallocate
     w->counters = headroom ? counters + counters / 4 + 1024 : counters;
     w->bytes = layout_workspace(ctx->cfg, w->rows, w->counters, &w->ml_off, &w->o_off);
@@ -342,6 +345,14 @@ const char* taper_strerror(int status) {
 }
 
 const char* taper_last_error(void) { return g_last_error.c_str(); }
+
+#ifdef TAPER_WG_TRACE
+int taper_wg_trace_buffer(taper_ctx* ctx, long long* buf) {
+    if (!ctx) return fail(TAPER_EINVAL, "null argument");
+    ctx->trace = buf;
+    return TAPER_OK;
+}
+#endif
 
 int taper_append_slots(int n_seqs, const int32_t* block_table, int bt_row_stride, const int32_t* prefix_len,
                        const int32_t* seg_start, const int32_t* seg_len, int page_size, int64_t n_pool_pages,

@@ -440,21 +440,13 @@ def test_config2_full_size(ctx_qwen):
     assert_parity(got, ref, "config2 full")
 
 
-def test_config3_full_size_sampled(ctx_qwen):
-    """Mixed batch at full size; the oracle checks every serial request's
-    neighbour-free sample: 4 serial sequences and each request's first and last
-    branch (all heads)."""
+def test_config3_full_size(ctx_qwen):
+    """Mixed batch at full size, default launch configuration, every output of all 68 sequences."""
     b = fill_values_numpy(structure_config3())
-    st = b.structure
-    got, _, _ = run_gpu(ctx_qwen, b, want_lse=False)
-    rows = [0, 5, 10, 15]
-    for g in range(16, st.n_groups):
-        m = np.flatnonzero(st.branch_group == g)
-        rows += [int(m[0]), int(m[-1])]
-    rows = np.array(sorted(set(rows)))
-    sub, pages = compact_rows(st, rows)
-    ref, _ = run_oracle(Batch(sub, b.q[rows], b.kv[pages]))
-    assert_parity(got[rows], ref, "config3 sampled")
+    ref, ref_lse = run_oracle(b)
+    got, lse, _ = run_gpu(ctx_qwen, b)
+    assert_parity(got, ref, "config3 full")
+    assert np.max(np.abs(lse - ref_lse)) <= 2e-3
 
 
 def sample_rows(st, n_serial=8):
@@ -489,7 +481,7 @@ def test_config4_long_context_sampled(ctx_qwen):
     assert_parity(got, ref, "config4 sampled")
 
 
-@pytest.mark.parametrize("k", [0, 4, 16])
+@pytest.mark.parametrize("k", [0, 2, 4, 8, 16])
 def test_config5_sweep_point_sampled(ctx_qwen, k):
     """One layer of the admission sweep at full size (96 serial + 32 parallel requests, width 1+k)."""
     import torch
@@ -587,9 +579,9 @@ def test_layer_launches_replay_from_a_captured_graph(ctx_qwen):
 
 @pytest.mark.parametrize("log2_scale", [9, 13])
 def test_large_values_of_v_pass_through_the_partials(ctx_qwen, log2_scale):
-    """Partial rows between workgroups are half precision after normalisation, so they stay inside the range of
-    V itself: V scaled by 2^9 and 2^13 (|V| up to about 3e4, below the half-precision limit) must give the
-    unscaled result times the same power of two, up to the rounding of values that were subnormal before."""
+    """V scaled by 2^9 and 2^13 (|V| up to about 3e4) must give the unscaled result times the same power of two
+    (partial rows between workgroups travel normalised and scaled row by row; larger factors and the fp32
+    format are covered in test_gpu_robustness.py)."""
     b = fill_values_numpy(structure_custom(QWEN, POOL_REQS, seed=141))
     base, _, _ = run_gpu(ctx_qwen, b, target_workgroups=2048, min_share_tokens=1)
     st, sh = b.structure, b.structure.shape

@@ -99,3 +99,55 @@ def test_decode_kernels_use_no_scratch_memory(tmp_path):
     decode = {k: v for k, v in seen.items() if "decode_kernel" in k}
     assert len(decode) == 12, sorted(seen)  # head_dim 64 / 128 x 1..3 row tiles per wave x 2 partial formats
     assert all(v == 0 for v in decode.values()), {k: v for k, v in decode.items() if v}
+
+
+class FakeTensor:
+    """What the binding looks at of a torch tensor (no GPU here)."""
+
+    class Dev:
+        def __init__(self, type_, index):
+            self.type, self.index = type_, index
+
+        def __repr__(self):
+            return f"{self.type}:{self.index}"
+
+    def __init__(self, numel, dtype="torch.bfloat16", contiguous=True, device=("cuda", 0)):
+        self._n, self.dtype, self._c, self.device = numel, dtype, contiguous, self.Dev(*device)
+
+    def numel(self):
+        return self._n
+
+    def is_contiguous(self):
+        return self._c
+
+    def data_ptr(self):
+        return 4096  # never dereferenced: the context is host-only, the library would answer TAPER_EHIP
+
+
+@pytest.mark.parametrize("what,bad", [
+    ("q", dict(numel=68 * 64 * 128 - 1)), ("q", dict(dtype="torch.float16")), ("q", dict(contiguous=False)),
+    ("q", dict(device=("cpu", None))), ("q", dict(device=("cuda", 1))),
+    ("kv", dict(numel=100)), ("kv", dict(dtype="torch.float32")),
+    ("out", dict(numel=5)), ("out", dict(contiguous=False)),
+    ("lse", dict(dtype="torch.bfloat16")), ("lse", dict(numel=68 * 64 - 1))])
+def test_binding_refuses_tensors_the_kernel_would_overrun(what, bad):
+    """dtype, contiguity, device and size are checked on the host, before any launch."""
+    st = structure_config3()
+    ctx = Context(64, 8, 128, device=-1)
+    plan = build(ctx, st)
+    ctx.cfg.device = 0  # pretend it is a device context: the tensor checks come before the library call
+    sizes = dict(q=st.n_seqs * 64 * 128, out=st.n_seqs * 64 * 128, kv=st.n_pool_pages * 2 * 8 * 16 * 128,
+                 lse=st.n_seqs * 64)
+    dtypes = dict(q="torch.bfloat16", out="torch.bfloat16", kv="torch.bfloat16", lse="torch.float32")
+    args = {}
+    for name in sizes:
+        kw = dict(numel=sizes[name], dtype=dtypes[name])
+        if name == what:
+            kw.update(bad)
+        args[name] = FakeTensor(**kw)
+    with pytest.raises(TaperError) as err:
+        ctx.decode_step_attention(plan, args["q"], args["kv"], args["out"], args["lse"], stream=0)
+    assert err.value.status == TAPER_EINVAL and {"kv": "kv_pages"}.get(what, what) in str(err.value)
+    ctx.cfg.device = -1
+    plan.free()
+    ctx.close()
