@@ -75,6 +75,18 @@ DEV bf16x8 softmax_block(f32x4 sx, f32x4 sy, float c, float& m, float& l, f32x4 
     return __builtin_convertvector(p, bf16x8);
 }
 
+// The accumulator a block's last matrix instruction wrote must not be read by a vector instruction
+// before the matrix pipeline has delivered it (eight passes; the hardware does not interlock, the
+// compiler inserts the wait states).  On a path that leaves the block's code through two branches
+// and starts with register copies of the accumulators, the compiler was seen to leave too few: the
+// last 16 dims of long private items came out wrong, in one build and not in another.  So a block
+// ends with the wait states written out, fenced so that the scheduler leaves them where they are.
+DEV void settle() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 11");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 DEV float sum_lane_groups(float v) {
     v += __shfl_xor(v, 16);
     v += __shfl_xor(v, 32);
@@ -248,7 +260,13 @@ DEV taper_merge_entry merge_entry(const StepArgs& a, const MergeMeta& mm, const 
 // groups of one wave may work on different sequences side by side.  Lane idx of the group owns
 // float4 columns c, c + LPR, ... (U of them) of one row, where LPR = D/4/U lanes cover a row;
 // n_thr / LPR rows are merged per pass.
-template <int D, int U, int R, int PF>
+//
+// ALL: every round issues R loads per column whatever is left of the list -- past the sequence's last
+// entry that entry once more, with weight zero -- so that a round has no branches (what the compiler
+// makes of R conditional loads needs many more registers; the callers that run half-waves side by
+// side have none to spare).  Otherwise only the entries that exist are loaded: every load here is a
+// full trip to memory through a saturated memory system, and the slowest one ends the round.
+template <int D, int U, int R, int PF, bool ALL>
 DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const int hk, const int e0, const int e1,
                     const int idx_, const int n_thr) {
     constexpr int LPR = D / 4 / U;
@@ -268,18 +286,21 @@ DEV void merge_rows(const StepArgs& a, const MergeMeta& mm, const int s, const i
             PartialRaw<PF> o[R][U];  // unpacked when they are used
 #pragma unroll
             for (int k = 0; k < R; ++k) {
-                // (past the sequence's last entry: that entry once more, with weight zero -- no branch, and the
-                // loads of a round are issued back to back)
                 const bool real = e + k < e1;
-                const taper_merge_entry me = merge_entry(a, mm, real ? e + k : e1 - 1);
-                const int row = me.first_row + hk * me.rows_per_head + (okr ? j : 0);
-                const float* rec = (const float*)((const char*)a.ws_ml + row * 16);
-                const float2 v = coherent_load2(rec);
-                ml[k] = real && okr ? v : make_float2(-INFINITY, 0.f);
+                ml[k] = make_float2(-INFINITY, 0.f);
                 sc[k] = 1.f;
-                if constexpr (PF == PF_F16S) sc[k] = coherent_load2(rec + 2).x;
 #pragma unroll
-                for (int u = 0; u < U; ++u) o[k][u] = partial_load4_raw<PF>(a.ws_o, row * D + 4 * (c0 + LPR * u));
+                for (int u = 0; u < U; ++u) o[k][u] = PartialRaw<PF>{};
+                if (ALL || real) {
+                    const taper_merge_entry me = merge_entry(a, mm, real ? e + k : e1 - 1);
+                    const int row = me.first_row + hk * me.rows_per_head + (okr ? j : 0);
+                    const float* rec = (const float*)((const char*)a.ws_ml + row * 16);
+                    const float2 v = coherent_load2(rec);
+                    if (real && okr) ml[k] = v;
+                    if constexpr (PF == PF_F16S) sc[k] = coherent_load2(rec + 2).x;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) o[k][u] = partial_load4_raw<PF>(a.ws_o, row * D + 4 * (c0 + LPR * u));
+                }
             }
             float mn = M;
 #pragma unroll
@@ -342,16 +363,16 @@ DEV void arrive_and_merge(const StepArgs& a, const MergeMeta& mm, int* todo, int
     const int n = *n_todo;
     // entries in flight per round: as many as leave the launch free of register spills (the streaming loops
     // of the callers are at the limit of the register file, and any scratch use costs microseconds per launch)
-    constexpr int R64 = PF == PF_F32 ? 6 : 8, R32 = PF == PF_F32 ? 2 : 4;
+    constexpr int R64 = 6, R32 = PF == PF_F32 ? 2 : 4;
     if (n <= 4) {
         if (wave < n) {
             const int b = todo[wave];
-            merge_rows<D, D / 32, R64, PF>(a, mm, item.seq0 + b, hk, mm.ms[b], mm.ms[b + 1], lane, 64);
+            merge_rows<D, D / 32, R64, PF, false>(a, mm, item.seq0 + b, hk, mm.ms[b], mm.ms[b + 1], lane, 64);
         }
     } else {
         for (int i = tid >> 5; i < n; i += 8) {
             const int b = todo[i];
-            merge_rows<D, D / 16, R32, PF>(a, mm, item.seq0 + b, hk, mm.ms[b], mm.ms[b + 1], tid & 31, 32);
+            merge_rows<D, D / 16, R32, PF, true>(a, mm, item.seq0 + b, hk, mm.ms[b], mm.ms[b + 1], tid & 31, 32);
         }
     }
 }
@@ -450,6 +471,9 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
             if (nv < 32) zero_tail(r.va, r.vb, qd, nv);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) O[dt] = mfma16(cat(r.va[dt], r.vb[dt]), pf, O[dt]);
+            // (at head_dim 128 the same statement here costs this loop a few spilled registers, and the code
+            // the compiler makes for it keeps the distance by itself; a build check scans every kernel for it)
+            if constexpr (D == 64) settle();
         };
 
         KVRegs<D> r0, r1;
@@ -537,7 +561,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
 #ifdef TAPER_WG_TRACE
         const long long t_m0 = wall_clock64();
 #endif
-        if (sm.last) merge_rows<D, 1, 8, PF>(a, sm.meta, item.seq0, hk, sm.meta.ms[0], sm.meta.ms[1], threadIdx.x, 256);
+        if (sm.last) merge_rows<D, 1, 8, PF, false>(a, sm.meta, item.seq0, hk, sm.meta.ms[0], sm.meta.ms[1], threadIdx.x, 256);
 #ifdef TAPER_WG_TRACE
         if (threadIdx.x == 0 && a.trace) a.trace[4 * blockIdx.x + 3] += wall_clock64() - t_m0;
 #endif
@@ -781,6 +805,7 @@ DEV void shared_path(const StepArgs& a, const int part, const int hk, SharedSmem
                             if (k < n_act) O[k][4 * h + i] = mfma16(vf, pf[k], O[k][4 * h + i]);
                     }
                 }
+                settle();
             }
         };
 
@@ -1005,6 +1030,7 @@ DEV void shared_path_wide(const StepArgs& a, const int part, const int hk, Share
                         if (k < n_act) O[k][4 * h + i] = mfma16(vf, pf[k], O[k][4 * h + i]);
                 }
             }
+            settle();
         };
 
         // (the previous item's LDS reads of these buffers ended before its closing barriers)

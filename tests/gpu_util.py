@@ -51,6 +51,11 @@ def assert_parity(got, ref, what=""):
     rms = float(np.sqrt(np.mean(ref ** 2)))
     mx, mean = float(err.max()), float(err.mean())
     print(f"[parity] {what}: max_abs={mx:.3e} mean_abs={mean:.3e} rms(ref)={rms:.3e} max_abs/rms={mx / rms:.3e}", flush=True)
+    if mx > MAX_ABS and err.ndim == 3:  # name the rows that are off: which sequences, which heads
+        per_row = err.max(axis=2)
+        bad = np.argwhere(per_row > MAX_ABS)
+        print(f"[parity] {what}: {len(bad)} (sequence, head) rows above the bar; first: "
+              + ", ".join(f"(s={s}, h={h}: {per_row[s, h]:.3e})" for s, h in bad[:: max(1, len(bad) // 24)]), flush=True)
     assert mx <= MAX_ABS, f"{what}: max-abs {mx} > {MAX_ABS}"
     assert mean <= MEAN_ABS, f"{what}: mean-abs {mean} > {MEAN_ABS}"
     # the absolute bar is loose for long contexts (outputs shrink like 1/sqrt(n)); bf16 rounding of the

@@ -1,15 +1,10 @@
 """CPU-only tests of the workspace bookkeeping (host-only contexts keep the same records as
 device contexts, without the device memory): a plan stays bound to the workspace it was built
 with whatever is built later, so that launches in flight and captured graphs keep valid
-addresses; and of the build itself: the decode kernels must not use scratch memory."""
-import os
-import re
-import subprocess
-
+addresses; and of the binding's checks of the tensors it is handed."""
 import pytest
 
 from paper_2605_06914_amd import Context, TaperError, TAPER_EINVAL
-from paper_2605_06914_amd.build import CSRC, HIP_FLAGS, ROOT
 from taper_inputs import AttnShape, structure_config2, structure_config3, structure_custom
 
 QWEN = AttnShape(64, 8, 128, 16)
@@ -76,29 +71,6 @@ def test_unknown_partial_format_is_rejected():
     assert err.value.status == TAPER_EINVAL
     for fmt in ("f16_scaled", "f32"):
         Context(64, 8, 128, device=-1, partial_format=fmt).close()
-
-
-def test_decode_kernels_use_no_scratch_memory(tmp_path):
-    """Any scratch use makes every launch set up scratch for the whole grid (microseconds per launch);
-    the kernels are written to fit the register file, and a change that spills must not go unnoticed."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    flags = [f for f in HIP_FLAGS if f not in ("-shared",)]
-    cmd = [hipcc, *flags, "--cuda-device-only", "-c", "-Rpass-analysis=kernel-resource-usage",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", str(tmp_path / "k.o"),
-           os.path.join(CSRC, "taper_kernels.hip")]
-    out = subprocess.run(cmd, capture_output=True, text=True, timeout=900)
-    assert out.returncode == 0, out.stderr[-2000:]
-    name, seen = None, {}
-    for line in out.stderr.splitlines():
-        m = re.search(r"Function Name: (\S+)", line)
-        if m:
-            name = m.group(1)
-        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
-        if m and name:
-            seen[name] = int(m.group(1))
-    decode = {k: v for k, v in seen.items() if "decode_kernel" in k}
-    assert len(decode) == 12, sorted(seen)  # head_dim 64 / 128 x 1..3 row tiles per wave x 2 partial formats
-    assert all(v == 0 for v in decode.values()), {k: v for k, v in decode.items() if v}
 
 
 class FakeTensor:
