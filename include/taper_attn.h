@@ -291,6 +291,31 @@ TAPER_API int taper_decode_step_attention_simple(taper_ctx *ctx, int n_seqs, con
                                        void *hip_stream);
 
 /*
+ * For callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: the operation and arguments of
+ * taper_decode_step_attention_simple, but the plan's device arrays and the partials
+ * workspace (counters, statistics, partial rows) live in a fixed 64 MiB array that is part
+ * of the library's device image, one copy per GPU, held until the process ends.  The call
+ * allocates and frees nothing, on the device or in pinned memory (its pinned staging buffer
+ * and the array's address are set up by taper_create), and unlike _simple it only enqueues
+ * (an upload of the plan, a clear of the counters, the decode kernel) and returns; the host
+ * arrays are read during the call only.  No lse output.
+ * TAPER_EINVAL with a message naming the sizes when the step needs more than the array holds
+ * (plan image above 8 MiB, or image + workspace above 64 MiB: the 64-layer admission-sweep batch at
+ * 640 sequences takes 30 MiB), TAPER_EHIP on a host-only context or when the array's address
+ * could not be looked up.
+ * All calls on one GPU, from any context, share that GPU's array, which keeps the previous
+ * call's contents: a call must not be enqueued before every earlier one on that GPU has been
+ * ordered before it (same stream, or an event); calls that overlap on one GPU race.
+ */
+TAPER_API int taper_decode_step_attention_static(taper_ctx *ctx, int n_seqs, const void *q /* device */,
+                                       const void *kv_pages /* device */, int64_t n_pool_pages,
+                                       const int32_t *block_table /* host */, int bt_row_stride,
+                                       const int32_t *branch_group /* host */, const int32_t *prefix_len /* host */,
+                                       const int32_t *suffix_len /* host */, void *out /* device */,
+                                       void *hip_stream);
+
+/*
  * Step-latency probe (paper App. C "Fitting": wall-clock latency of synthetic
  * steps; §2.3: externality E = T(S(k)) - T(S0)).  Runs `warmup` untimed and
  * `iters` timed steps; a step enqueues the attention of n_layers layers (layer l

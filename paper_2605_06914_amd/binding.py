@@ -26,7 +26,7 @@ EXPORTED = [
     "taper_plan_build_segments", "taper_append_slots", "taper_kv_append", "taper_branch_blocks",
     "taper_predictor_fit", "taper_predictor_eval", "taper_predictor_mape", "taper_window_create",
     "taper_window_destroy", "taper_window_push", "taper_window_size", "taper_window_fit", "taper_admit_step",
-    "taper_stream_read_probe", "taper_reserve",
+    "taper_stream_read_probe", "taper_reserve", "taper_decode_step_attention_static",
 ]
 
 
@@ -136,6 +136,7 @@ def load_library() -> ctypes.CDLL:
     lib.taper_plan_resolve_slots.argtypes = [vp, vp, vp, i64, vp]
     lib.taper_decode_step_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.taper_decode_step_attention_simple.argtypes = [vp, ci, vp, vp, i64, vp, ci, vp, vp, vp, vp, vp]
+    lib.taper_decode_step_attention_static.argtypes = [vp, ci, vp, vp, i64, vp, ci, vp, vp, vp, vp, vp]
     lib.taper_step_latency_probe.argtypes = [vp, vp, ci, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                              ci, ci, vp, ctypes.POINTER(taper_probe_result)]
     lib.taper_kernel_times.argtypes = [vp, vp, vp, vp, vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
@@ -367,6 +368,16 @@ class Context:
         grp, pl, sl = _i32(branch_group), _i32(prefix_len), _i32(suffix_len)
         pq, pkv, pout, _ = self._step_ptrs(bt.shape[0], n_pool_pages, q, kv_pages, out)
         _check(load_library().taper_decode_step_attention_simple(
+            self._h, bt.shape[0], pq, pkv, int(n_pool_pages), bt.ctypes.data, bt.shape[1],
+            grp.ctypes.data, pl.ctypes.data, sl.ctypes.data, pout, _stream(stream)))
+
+    def decode_step_attention_static(self, q, kv_pages, n_pool_pages, block_table, branch_group, prefix_len,
+                                     suffix_len, out, stream=None):
+        """The same step through the library's static scratch array: allocates nothing, enqueues only."""
+        bt = _i32(block_table)
+        grp, pl, sl = _i32(branch_group), _i32(prefix_len), _i32(suffix_len)
+        pq, pkv, pout, _ = self._step_ptrs(bt.shape[0], n_pool_pages, q, kv_pages, out)
+        _check(load_library().taper_decode_step_attention_static(
             self._h, bt.shape[0], pq, pkv, int(n_pool_pages), bt.ctypes.data, bt.shape[1],
             grp.ctypes.data, pl.ctypes.data, sl.ctypes.data, pout, _stream(stream)))
 

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libtaper_attn.so")
-SOURCES = ["taper_kernels.hip", "taper_api.cpp", "taper_plan.cpp", "taper_admission.cpp"]
+SOURCES = ["taper_kernels.hip", "taper_static.hip", "taper_api.cpp", "taper_plan.cpp", "taper_admission.cpp"]
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
     # never let the compiler form packed-fp32 instructions

@@ -34,6 +34,8 @@ int fail_hip(hipError_t e, const char* what) {
     } while (0)
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// largest plan image taper_decode_step_attention_static uploads (block table and work lists of one step)
+constexpr size_t kStaticImageBytes = (size_t)8 << 20;
 }  // namespace
 
 namespace taper {
@@ -84,6 +86,12 @@ struct taper_ctx {
     bool counters_suspect = false;  // a call reported a HIP error: clear every workspace's counters before the next launch
     std::vector<PlanBuffers> free_buffers;
     int default_workgroups = 0;  // two resident workgroups per compute unit of the device (0: the builder's own default)
+    // for taper_decode_step_attention_static: the device's copy of the library's scratch array, and a pinned
+    // image of the plan that is uploaded into it (made at taper_create: the call itself allocates nothing)
+    void* static_scratch = nullptr;
+    std::string static_error;  // why static_scratch is null
+    void* static_staging = nullptr;
+    hipEvent_t static_uploaded = nullptr;
 #ifdef TAPER_WG_TRACE
     long long* trace = nullptr;
 #endif
@@ -421,6 +429,15 @@ int taper_create(const taper_attn_config* cfg, taper_ctx** out_ctx) {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, cfg->device) == hipSuccess && cus > 0)
             ctx->default_workgroups = 2 * cus;  // the decode kernel keeps two workgroups resident per compute unit
+        // set-up of the entry point that allocates nothing (cfg->device is current)
+        e = taper::static_scratch(cfg->device, &ctx->static_scratch);
+        if (e == hipSuccess) e = hipHostMalloc(&ctx->static_staging, kStaticImageBytes, hipHostMallocDefault);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->static_uploaded, hipEventDisableTiming);
+        if (e != hipSuccess) {  // the other entry points do not need it: the static one reports this
+            ctx->static_error = std::string("static scratch set-up: ") + hipGetErrorString(e);
+            ctx->static_scratch = nullptr;
+            (void)hipGetLastError();
+        }
     }
     *out_ctx = ctx;
     return TAPER_OK;
@@ -431,6 +448,8 @@ void taper_destroy(taper_ctx* ctx) {
     if (!ctx->host_only) (void)hipDeviceSynchronize();
     for (Workspace* w : ctx->workspaces) release_workspace(w);
     for (PlanBuffers& b : ctx->free_buffers) destroy_buffers(b);
+    if (ctx->static_uploaded) (void)hipEventDestroy(ctx->static_uploaded);
+    if (ctx->static_staging) (void)hipHostFree(ctx->static_staging);
     delete ctx;
 }
 
@@ -598,6 +617,49 @@ int taper_decode_step_attention_simple(taper_ctx* ctx, int n_seqs, const void* q
     }
     taper_plan_free(plan);
     return st;
+}
+
+int taper_decode_step_attention_static(taper_ctx* ctx, int n_seqs, const void* q, const void* kv_pages,
+                                       int64_t n_pool_pages, const int32_t* block_table, int bt_row_stride,
+                                       const int32_t* branch_group, const int32_t* prefix_len,
+                                       const int32_t* suffix_len, void* out, void* hip_stream) {
+    if (!ctx || !q || !kv_pages || !out || !suffix_len || n_seqs < 1) return fail(TAPER_EINVAL, "null argument");
+    if (ctx->host_only) return fail(TAPER_EHIP, "host-only context: no device work possible");
+    if (!ctx->static_scratch) return fail(TAPER_EHIP, ctx->static_error.empty() ? "static scratch unavailable" : ctx->static_error);
+    // the plan, on the host (host memory only)
+    taper::HostPlan h;
+    std::string err;
+    taper_plan_options o;
+    std::memset(&o, 0, sizeof o);
+    o.share_prefix = 1;
+    o.target_workgroups = ctx->default_workgroups;
+    int st = taper::build_host_plan(ctx->cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len, suffix_len,
+                                    n_pool_pages, &o, &h, &err);
+    if (st != TAPER_OK) return fail(st, err);
+    // layout inside the array: plan image | counters | statistics | partial rows
+    ImagePiece pieces[10];
+    const size_t image = layout_image(h, pieces);
+    size_t ml_off = 0, o_off = 0;
+    const int64_t counters = counters_needed(ctx->cfg, h.n_seqs);
+    const size_t ws_bytes = layout_workspace(ctx->cfg, h.n_partial_rows, counters, &ml_off, &o_off);
+    if (image > kStaticImageBytes || image + ws_bytes > taper::kStaticScratchBytes)
+        return fail(TAPER_EINVAL, "step too large for the static scratch array: plan image " + std::to_string(image) +
+                                      " bytes (limit " + std::to_string(kStaticImageBytes) + "), image + workspace " +
+                                      std::to_string(image + ws_bytes) + " bytes (limit " +
+                                      std::to_string(taper::kStaticScratchBytes) + ")");
+    hipStream_t s = (hipStream_t)hip_stream;
+    HIP_TRY(hipSetDevice(ctx->cfg.device));
+    HIP_TRY(hipEventSynchronize(ctx->static_uploaded));  // the previous call's upload has read the pinned image
+    write_image(pieces, ctx->static_staging);
+    char* base = (char*)ctx->static_scratch;
+    HIP_TRY(hipMemcpyAsync(base, ctx->static_staging, image, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipEventRecord(ctx->static_uploaded, s));
+    // the array keeps the last call's contents: what must start at zero is cleared (the counters)
+    char* ws = base + image;
+    HIP_TRY(taper::launch_zero_words((int32_t*)ws, counters, s));
+    const taper::StepArgs a = make_args(ctx, h, bind_image(pieces, base), ws, ml_off, o_off, q, kv_pages, out, nullptr);
+    HIP_TRY(taper::launch_decode(a, s));
+    return TAPER_OK;
 }
 
 int taper_step_latency_probe(taper_ctx* ctx, const taper_plan* plan, int n_layers, const void* const* q_per_layer,

@@ -44,6 +44,12 @@ struct StepArgs {
 };
 
 
+// Device memory that belongs to no context: the scratch array of taper_decode_step_attention_static.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+// Address of the calling device's copy of the array (looked up once per device; `device` must be current).
+hipError_t static_scratch(int device, void** ptr);
+hipError_t launch_zero_words(int32_t* p, int64_t n, hipStream_t s);
+
 hipError_t launch_decode(const StepArgs& a, hipStream_t s);
 hipError_t launch_kv_append(const void* k_new, const void* v_new, const int64_t* slot, void* kv, int n_seqs, int n_kv_heads,
                             int head_dim, hipStream_t s);
