@@ -34,6 +34,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="layers per step (0 = workload default)")
     ap.add_argument("--target-workgroups", type=int, default=0)
     ap.add_argument("--shared-cost-pct", type=int, default=0)
+    ap.add_argument("--plan-options", default="{}", help="further plan options as JSON, e.g. '{\"pool_pct\": 30}'")
     ap.add_argument("--no-share", action="store_true", help="every branch streams its prefix itself (for comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-read-ceiling", action="store_true", help="skip the plain streaming-read measurement")
@@ -491,6 +492,7 @@ def main():
     ctx = Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, device=0, partial_format=args.partial_format)
     plan_kw = dict(target_workgroups=args.target_workgroups, share_prefix=not args.no_share,
                    shared_cost_pct=args.shared_cost_pct)
+    plan_kw.update(json.loads(args.plan_options))
 
     def step():
         plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages, **plan_kw)

@@ -575,12 +575,19 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
 template <int D, int PF>
 DEV void private_items(const StepArgs& a, int it0, const int it1, const int hk, PrivateSmem<D>& sm) {
     const int wgs_per_head = a.n_parts_shared + a.n_parts_private;  // = gridDim.x / n_kv_heads
+#ifdef TAPER_WG_TRACE
+    bool turned = false;
+#endif
     for (;;) {
         int it = it0;
         if (it0 < it1) {
             ++it0;
         } else {
             if (a.n_pool_items == 0) return;
+#ifdef TAPER_WG_TRACE
+            if (threadIdx.x == 0 && a.trace && !turned) a.trace[4 * blockIdx.x + 1] = wall_clock64();  // own share done
+            turned = true;
+#endif
             if (threadIdx.x == 0) sm.pick = atomicAdd(a.pool_ctr + hk, 1);
             __syncthreads();
             const int i = sm.pick;
@@ -1072,7 +1079,7 @@ __global__ __launch_bounds__(256, (NTW <= 2 || D == 128 ? 2 : 1)) void decode_ke
     __shared__ __attribute__((aligned(16))) char smem_raw[sizeof(Smem)];
     const int part = blockIdx.x / a.n_kv_heads;
     const int hk = blockIdx.x % a.n_kv_heads;
-#ifdef TAPER_WG_TRACE  // trace builds only (wg_trace.py): per-workgroup clocks -- start, shared share done, left, time in merges
+#ifdef TAPER_WG_TRACE  // trace builds only (wg_trace.py): per-workgroup clocks -- start, own share done, left, time in merges
     long long* trace = a.trace;
     if (threadIdx.x == 0 && trace) trace[4 * blockIdx.x] = wall_clock64();
 #endif
@@ -1088,7 +1095,7 @@ __global__ __launch_bounds__(256, (NTW <= 2 || D == 128 ? 2 : 1)) void decode_ke
         it1 = a.part_start[part + 1];
     }
 #ifdef TAPER_WG_TRACE
-    if (threadIdx.x == 0 && trace) trace[4 * blockIdx.x + 1] = wall_clock64();  // shared share done / private share about to start
+    if (threadIdx.x == 0 && trace) trace[4 * blockIdx.x + 1] = wall_clock64();  // shared share done (a private share: overwritten when it is done)
 #endif
     private_items<D, PF>(a, it0, it1, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
 #ifdef TAPER_WG_TRACE
