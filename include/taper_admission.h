@@ -40,6 +40,18 @@ typedef struct {
 TAPER_API int taper_predictor_fit(int64_t n, const double *n_tokens, const double *l_context, const double *t_ms,
                                   taper_predictor *out, double *mape_pct);
 
+/*
+ * The same fit under b >= 0 and c >= 0 (App. C "Monotonicity": the predictor is monotone in admitted
+ * branches because b and c are positive; the planner's pruning rule relies on it and taper_admit_step
+ * refuses a predictor that is not).  Noisy or small observation sets -- a rolling window of steps that
+ * are all launch-bound, say -- can give ordinary least squares a negative slope; this form returns the
+ * least-squares solution over the region b, c >= 0 instead (equal to the ordinary one whenever that is
+ * inside it; otherwise one or both coefficients are exactly 0 and the rest is refitted), so a refresh
+ * never hands the planner a model it cannot use.  Same errors as taper_predictor_fit.
+ */
+TAPER_API int taper_predictor_fit_monotone(int64_t n, const double *n_tokens, const double *l_context,
+                                           const double *t_ms, taper_predictor *out, double *mape_pct);
+
 TAPER_API double taper_predictor_eval(const taper_predictor *p, double n_tokens, double l_context);
 
 /* Mean absolute percentage error of p over n observations (App. C "Accuracy"). */
@@ -57,6 +69,8 @@ TAPER_API void taper_window_destroy(taper_window *w);
 TAPER_API int taper_window_push(taper_window *w, double n_tokens, double l_context, double t_ms);
 TAPER_API int32_t taper_window_size(const taper_window *w);
 TAPER_API int taper_window_fit(const taper_window *w, taper_predictor *out, double *mape_pct);
+/* The refresh a planner should use: taper_predictor_fit_monotone over the window. */
+TAPER_API int taper_window_fit_monotone(const taper_window *w, taper_predictor *out, double *mape_pct);
 
 /* Utility curve u_r(k) of §3.3: what k opportunistic branches are worth to request r. */
 typedef enum {

@@ -38,6 +38,21 @@ def predictor_fit(n_tokens, l_context, t_ms):
     return float(beta[0]), float(beta[1]), float(beta[2])
 
 
+def predictor_fit_monotone(n_tokens, l_context, t_ms):
+    """The fit under b >= 0, c >= 0 (App. C, "Monotonicity": T must be monotone in admitted branches).
+    Definition: minimise ||X beta - t||_2 over that region; the library's bounded least squares is the step
+    (columns scaled to unit max so that its tolerances mean the same for both regressors)."""
+    from scipy.optimize import lsq_linear
+
+    n = np.asarray(n_tokens, np.float64)
+    L = np.asarray(l_context, np.float64)
+    t = np.asarray(t_ms, np.float64)
+    sn, sL = np.abs(n).max(), np.abs(L).max()
+    X = np.stack([np.ones_like(n), n / sn, L / sL], axis=1)
+    r = lsq_linear(X, t, bounds=([-np.inf, 0.0, 0.0], [np.inf, np.inf, np.inf]), method="bvls", tol=1e-14)
+    return float(r.x[0]), float(r.x[1] / sn), float(r.x[2] / sL)
+
+
 def predictor_eval(coef, n_tokens, l_context):
     a, b, c = coef
     return a + b * n_tokens + c * l_context
@@ -95,39 +110,43 @@ class StepPlan:
 
 
 def taper_step(requests: Sequence[Request], coef, rho: float) -> StepPlan:
-    """Greedy widening of the protected composition (§3.4): repeatedly admit the ready
-    branch with the best marginal utility per marginal predicted latency among those
-    whose widened step still fits the slack budget; a request whose next branch does
-    not fit is dropped for good (T is monotone)."""
-    T = lambda n, L: predictor_eval(coef, n, L)
-    n = len(requests)
-    L = sum(r.base_context for r in requests)
-    t0 = T(n, L)
+    """Per-step admission as the definitions state it (§3.3, §3.4).
+
+    The step starts as the protected composition S_0 and is widened one branch at a time.  In every round:
+      1. feasibility (§3.3): of the requests still under consideration, those whose widened step would keep
+         T(S) within the budget T_0 + rho * B_t form the feasible set; the others leave for good (T is
+         monotone in admitted branches, so nothing of theirs can fit later);
+      2. selection (§3.4): among the feasible ones the branch with the largest marginal utility per marginal
+         predicted latency is admitted -- unless that best ratio is not positive, or nothing is feasible,
+         which ends the step.
+    A request with no ready branch left is no longer under consideration."""
+    T = lambda comp: predictor_eval(coef, comp[0], comp[1])
+    step = (len(requests), sum(r.base_context for r in requests))  # (n_tokens, L_context) of S_0
+    t0 = T(step)
     budget = slack_budget(t0, min(r.slack_ms for r in requests), rho)
     granted = [0] * len(requests)
-    live = [i for i, r in enumerate(requests) if len(r.branch_context) > 0]
-    t_step = t0
-    evals = 0
-    while live:
-        best = None
-        still = []
-        for i in live:
-            r = requests[i]
-            n_w, L_w = n + 1, L + r.branch_context[granted[i]]
-            t_w = T(n_w, L_w)
-            evals += 1
-            if t_w > budget:
-                continue  # pruned: no later branch of r can fit either
-            still.append(i)
-            du = r.utility(granted[i] + 1) - r.utility(granted[i])
-            score = du / (EPS + max(0.0, t_w - t_step))
-            if best is None or score > best[0]:
-                best = (score, i, n_w, L_w, t_w)
-        live = still
-        if best is None or best[0] <= 0:
+    considered = [i for i, r in enumerate(requests) if r.branch_context]
+    t_step, evaluations = t0, 0
+
+    def widened(i):
+        return (step[0] + 1, step[1] + requests[i].branch_context[granted[i]])
+
+    def ratio(i, t_widened):
+        gain = requests[i].utility(granted[i] + 1) - requests[i].utility(granted[i])
+        return gain / (EPS + max(0.0, t_widened - t_step))
+
+    while considered:
+        priced = {i: T(widened(i)) for i in considered}  # one evaluation of T per request and round
+        evaluations += len(priced)
+        feasible = [i for i in considered if priced[i] <= budget]
+        if not feasible:
             break
-        _, i, n, L, t_step = best
-        granted[i] += 1
-        if granted[i] >= len(requests[i].branch_context):
-            live.remove(i)
-    return StepPlan(granted, n, L, t0, budget, t_step, evals)
+        ratios = [ratio(i, priced[i]) for i in feasible]
+        top = max(ratios)
+        if top <= 0:
+            break
+        chosen = feasible[ratios.index(top)]  # the earliest request among equals
+        step, t_step = widened(chosen), priced[chosen]
+        granted[chosen] += 1
+        considered = [i for i in feasible if granted[i] < len(requests[i].branch_context)]
+    return StepPlan(granted, step[0], step[1], t0, budget, t_step, evaluations)

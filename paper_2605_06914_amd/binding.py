@@ -26,6 +26,7 @@ EXPORTED = [
     "taper_plan_build_segments", "taper_append_slots", "taper_kv_append", "taper_branch_blocks",
     "taper_predictor_fit", "taper_predictor_eval", "taper_predictor_mape", "taper_window_create",
     "taper_window_destroy", "taper_window_push", "taper_window_size", "taper_window_fit", "taper_admit_step",
+    "taper_predictor_fit_monotone", "taper_window_fit_monotone",
     "taper_stream_read_probe", "taper_reserve", "taper_decode_step_attention_static",
 ]
 
@@ -146,6 +147,8 @@ def load_library() -> ctypes.CDLL:
     dp, f64 = ctypes.POINTER(ctypes.c_double), ctypes.c_double
     pp = ctypes.POINTER(taper_predictor)
     lib.taper_predictor_fit.argtypes = [i64, vp, vp, vp, pp, dp]
+    lib.taper_predictor_fit_monotone.argtypes = [i64, vp, vp, vp, pp, dp]
+    lib.taper_window_fit_monotone.argtypes = [vp, pp, dp]
     lib.taper_predictor_eval.argtypes = [pp, f64, f64]
     lib.taper_predictor_eval.restype = f64
     lib.taper_predictor_mape.argtypes = [pp, i64, vp, vp, vp, dp]
@@ -428,14 +431,16 @@ def _f64(a) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.float64)
 
 
-def predictor_fit(n_tokens, l_context, t_ms):
-    """(a, b, c) of T = a + b n_tokens + c L_context by least squares, and the fit's MAPE in percent."""
+def predictor_fit(n_tokens, l_context, t_ms, monotone: bool = False):
+    """(a, b, c) of T = a + b n_tokens + c L_context by least squares (under b, c >= 0 if monotone), and the
+    fit's MAPE in percent."""
     lib = load_library()
     n, L, t = _f64(n_tokens), _f64(l_context), _f64(t_ms)
     if not (n.shape == L.shape == t.shape and n.ndim == 1):
         raise ValueError("n_tokens, l_context, t_ms must be 1-D arrays of one length")
     p, m = taper_predictor(), ctypes.c_double()
-    _check(lib.taper_predictor_fit(len(n), n.ctypes.data, L.ctypes.data, t.ctypes.data, ctypes.byref(p), ctypes.byref(m)))
+    fit = lib.taper_predictor_fit_monotone if monotone else lib.taper_predictor_fit
+    _check(fit(len(n), n.ctypes.data, L.ctypes.data, t.ctypes.data, ctypes.byref(p), ctypes.byref(m)))
     return (p.a, p.b, p.c), m.value
 
 
@@ -467,9 +472,10 @@ class Window:
     def __len__(self):
         return self._lib.taper_window_size(self._h)
 
-    def fit(self):
+    def fit(self, monotone: bool = False):
         p, m = taper_predictor(), ctypes.c_double()
-        _check(self._lib.taper_window_fit(self._h, ctypes.byref(p), ctypes.byref(m)))
+        fit = self._lib.taper_window_fit_monotone if monotone else self._lib.taper_window_fit
+        _check(fit(self._h, ctypes.byref(p), ctypes.byref(m)))
         return (p.a, p.b, p.c), m.value
 
     def close(self):

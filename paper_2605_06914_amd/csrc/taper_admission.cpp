@@ -3,6 +3,8 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstddef>
+#include <cstdint>
 #include <new>
 #include <string>
 #include <vector>
@@ -106,6 +108,63 @@ int taper_predictor_fit(int64_t n, const double* n_tokens, const double* l_conte
     return TAPER_OK;
 }
 
+int taper_predictor_fit_monotone(int64_t n, const double* n_tokens, const double* l_context, const double* t_ms,
+                                 taper_predictor* out, double* mape_pct) {
+    if (!n_tokens || !l_context || !t_ms || !out) return set_error(TAPER_EINVAL, "null argument");
+    double beta[3];
+    if (int rc = ols3(n, n_tokens, l_context, t_ms, beta)) return rc;
+    if (beta[1] < 0 || beta[2] < 0) {
+        // Two sign constraints: the minimiser has one or both of them active.  Each active set is a smaller
+        // least-squares problem in closed form; the best feasible one is the constrained minimiser (the
+        // objective is convex, so a feasible stationary point on a face is the minimum over that face).
+        double sn = 0, sL = 0, st = 0, snn = 0, sLL = 0, snt = 0, sLt = 0;
+        const double N = (double)n;
+        for (int64_t i = 0; i < n; ++i) {
+            sn += n_tokens[i];
+            sL += l_context[i];
+            st += t_ms[i];
+        }
+        const double mn = sn / N, mL = sL / N, mt = st / N;
+        for (int64_t i = 0; i < n; ++i) {  // centred sums: well conditioned for regressors of any magnitude
+            const double dn = n_tokens[i] - mn, dL = l_context[i] - mL, dt = t_ms[i] - mt;
+            snn += dn * dn;
+            sLL += dL * dL;
+            snt += dn * dt;
+            sLt += dL * dt;
+        }
+        auto rss = [&](double a_, double b_, double c_) {
+            double acc = 0;
+            for (int64_t i = 0; i < n; ++i) {
+                const double e = a_ + b_ * n_tokens[i] + c_ * l_context[i] - t_ms[i];
+                acc += e * e;
+            }
+            return acc;
+        };
+        double best[3] = {mt, 0.0, 0.0};  // both active: the mean
+        double best_rss = rss(best[0], 0.0, 0.0);
+        if (snn > 0) {  // c = 0: line in n_tokens
+            const double b_ = snt / snn;
+            if (b_ >= 0) {
+                const double a_ = mt - b_ * mn, v = rss(a_, b_, 0.0);
+                if (v < best_rss) best[0] = a_, best[1] = b_, best[2] = 0.0, best_rss = v;
+            }
+        }
+        if (sLL > 0) {  // b = 0: line in L_context
+            const double c_ = sLt / sLL;
+            if (c_ >= 0) {
+                const double a_ = mt - c_ * mL, v = rss(a_, 0.0, c_);
+                if (v < best_rss) best[0] = a_, best[1] = 0.0, best[2] = c_, best_rss = v;
+            }
+        }
+        beta[0] = best[0], beta[1] = best[1], beta[2] = best[2];
+    }
+    out->a = beta[0];
+    out->b = beta[1];
+    out->c = beta[2];
+    if (mape_pct) return mape(*out, n, n_tokens, l_context, t_ms, mape_pct);
+    return TAPER_OK;
+}
+
 double taper_predictor_eval(const taper_predictor* p, double n_tokens, double l_context) {
     return p ? eval(*p, n_tokens, l_context) : NAN;
 }
@@ -147,6 +206,11 @@ int taper_window_fit(const taper_window* w, taper_predictor* out, double* mape_p
     return taper_predictor_fit(w->size, w->n.data(), w->L.data(), w->t.data(), out, mape_pct);
 }
 
+int taper_window_fit_monotone(const taper_window* w, taper_predictor* out, double* mape_pct) {
+    if (!w || !out) return set_error(TAPER_EINVAL, "null argument");
+    return taper_predictor_fit_monotone(w->size, w->n.data(), w->L.data(), w->t.data(), out, mape_pct);
+}
+
 int taper_admit_step(const taper_predictor* T, int32_t n_requests, const int64_t* base_context, const double* slack_ms,
                      const int32_t* branch_start, const int64_t* branch_context, const double* weight,
                      const double* utility_table, const taper_admission_options* opts, int32_t* granted,
@@ -181,43 +245,55 @@ int taper_admit_step(const taper_predictor* T, int32_t n_requests, const int64_t
 
     const double t0 = eval(*T, (double)n, (double)L);
     const double budget = t0 + opts->rho * std::max(0.0, min_slack - t0);
-    std::vector<int> live;
+    // The candidates: one record per request that still has a ready branch and has not been pruned, holding
+    // what the next round needs of it -- the context its next branch would add and what that branch is worth.
+    // Only the record of the request that was just widened changes between rounds.
+    struct Candidate {
+        int32_t request;
+        int64_t next_context;
+        double gain;  // u(k + 1) - u(k) at the request's current k
+    };
+    std::vector<Candidate> cand;
+    cand.reserve(n_requests);
     for (int r = 0; r < n_requests; ++r) {
         granted[r] = 0;
-        if (branch_start[r + 1] > branch_start[r]) live.push_back(r);
+        if (branch_start[r + 1] > branch_start[r])
+            cand.push_back({r, branch_context[branch_start[r]], utility(r, 1) - utility(r, 0)});
     }
     double t_step = t0;
     int64_t evals = 0, admitted = 0;
-    while (!live.empty()) {
-        int best = -1;
+    while (!cand.empty()) {
+        // one sweep: price every candidate's widened step, let those over the budget go for good (T only grows),
+        // remember the best ratio among the rest (the earliest request on a tie)
+        size_t kept = 0, best = SIZE_MAX;
         double best_score = 0, best_t = 0;
-        int64_t best_L = 0;
-        size_t kept = 0;
-        for (size_t q = 0; q < live.size(); ++q) {
-            const int r = live[q];
-            const int64_t L_w = L + branch_context[branch_start[r] + granted[r]];
-            const double t_w = eval(*T, (double)(n + 1), (double)L_w);
+        for (size_t q = 0; q < cand.size(); ++q) {
+            const double t_w = eval(*T, (double)(n + 1), (double)(L + cand[q].next_context));
             ++evals;
-            if (t_w > budget) continue;  // pruned for good
-            live[kept++] = r;
-            const double du = utility(r, granted[r] + 1) - utility(r, granted[r]);
-            const double score = du / (1e-9 + std::max(0.0, t_w - t_step));
-            if (best < 0 || score > best_score) {
-                best = r;
+            if (t_w > budget) continue;
+            const double score = cand[q].gain / (1e-9 + std::max(0.0, t_w - t_step));
+            if (best == SIZE_MAX || score > best_score) {
+                best = kept;
                 best_score = score;
                 best_t = t_w;
-                best_L = L_w;
             }
+            cand[kept++] = cand[q];
         }
-        live.resize(kept);
-        if (best < 0 || !(best_score > 0)) break;
+        cand.resize(kept);
+        if (best == SIZE_MAX || !(best_score > 0)) break;
+        Candidate& c = cand[best];
+        const int r = c.request;
         n += 1;
-        L = best_L;
+        L += c.next_context;
         t_step = best_t;
-        ++granted[best];
         ++admitted;
-        if (granted[best] >= branch_start[best + 1] - branch_start[best])
-            live.erase(std::find(live.begin(), live.end(), best));
+        const int k = ++granted[r];
+        if (k >= branch_start[r + 1] - branch_start[r]) {
+            cand.erase(cand.begin() + (ptrdiff_t)best);  // (keeps the index order the tie rule needs)
+        } else {
+            c.next_context = branch_context[branch_start[r] + k];
+            c.gain = utility(r, k + 1) - utility(r, k);
+        }
     }
     result->t0_ms = t0;
     result->budget_ms = budget;

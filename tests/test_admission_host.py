@@ -28,6 +28,52 @@ def test_fit_matches_oracle(noise):
     assert predictor_eval(coef, 100, 50000) == pytest.approx(ora.predictor_eval(ref, 100, 50000), rel=1e-12)
 
 
+def probe_like_observations(seed):
+    """16 steps (batch 1-64 x context 128-8192) whose small ones are launch-bound and noisy."""
+    rng = np.random.default_rng(seed)
+    n = np.repeat([1.0, 4.0, 16.0, 64.0], 4)
+    L = n * np.tile([128.0, 1024.0, 4096.0, 8192.0], 4)
+    t = 0.03 + 1.2e-6 * L + rng.normal(-2e-4, 3e-4) * n + rng.normal(0, 2e-3, 16)
+    return n, L, t
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_monotone_fit_matches_oracle_and_is_usable_by_the_planner(seed):
+    """A refresh never hands the planner a model it refuses: b, c >= 0, equal to the oracle's bounded least
+    squares, and equal to the plain fit whenever that is monotone already."""
+    n, L, t = probe_like_observations(seed)
+    coef, mape = predictor_fit(n, L, t, monotone=True)
+    ref = ora.predictor_fit_monotone(n, L, t)
+    assert np.allclose(coef, ref, rtol=1e-6, atol=1e-11), (coef, ref)
+    assert coef[1] >= 0 and coef[2] >= 0
+    assert mape == pytest.approx(ora.mape_pct(coef, n, L, t), rel=1e-9)
+    free, _ = predictor_fit(n, L, t)
+    if free[1] >= 0 and free[2] >= 0:
+        assert np.allclose(coef, free, rtol=1e-9, atol=1e-13)
+    else:
+        assert coef[1] == 0.0 or coef[2] == 0.0
+        with pytest.raises(TaperError):  # the plain fit is what the planner refuses
+            admit_step(free, [100, 100], [1e3, 1e3], [[50], []])
+    granted, res = admit_step(coef, [100, 100], [1e3, 1e3], [[50], []])
+    assert granted.tolist() == [1, 0] and np.isfinite(res["t_pred_ms"])
+
+
+def test_some_probe_like_sets_do_need_the_constraint():
+    assert any(predictor_fit(*probe_like_observations(s))[0][1] < 0 for s in range(12))
+
+
+def test_window_refresh_is_monotone():
+    w = Window(16)
+    n, L, t = probe_like_observations(next(s for s in range(12) if predictor_fit(*probe_like_observations(s))[0][1] < 0))
+    for x in zip(n, L, t):
+        w.push(*x)
+    free, _ = w.fit()
+    coef, _ = w.fit(monotone=True)
+    assert free[1] < 0 and coef[1] == 0.0 and coef[2] > 0
+    assert np.allclose(coef, ora.predictor_fit_monotone(n, L, t), rtol=1e-6, atol=1e-11)
+    w.close()
+
+
 def test_fit_hand_example():
     coef, mape = predictor_fit([1, 1, 3, 3], [1, 3, 1, 3], [2, 4, 6, 12])
     assert np.allclose(coef, (-4, 3, 2), atol=1e-12) and mape == pytest.approx(25.0)

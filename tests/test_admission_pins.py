@@ -211,7 +211,69 @@ def pin_table_utility_and_zero_gain_stops(m):
     assert m.taper_step(reqs, COEF, 1.0).granted == [1]
 
 
-PINS = [pin_ols_by_hand, pin_exact_recovery_on_the_paper_grid, pin_residual_is_orthogonal_to_the_regressors,
+def _kkt(coef, n, L, t):
+    """Optimality of a fit over the region b, c >= 0: the gradient of the squared error vanishes along the
+    free coordinates and points into the region along the clamped ones."""
+    n, L, t = (np.asarray(x, np.float64) for x in (n, L, t))
+    res = coef[0] + coef[1] * n + coef[2] * L - t
+    g = np.array([res.sum(), (res * n).sum(), (res * L).sum()])
+    scale = np.array([len(t), np.abs(n).sum(), np.abs(L).sum()]) * np.abs(t).max()
+    assert abs(g[0]) <= 1e-9 * scale[0]
+    for k in (1, 2):
+        assert coef[k] >= 0
+        if coef[k] > 0:
+            assert abs(g[k]) <= 1e-9 * scale[k]
+        else:
+            assert g[k] >= -1e-9 * scale[k]
+
+
+def pin_monotone_fit_equals_ols_inside_the_region(m):
+    rng = np.random.default_rng(5)
+    n = rng.integers(1, 512, 60).astype(float)
+    L = n * rng.integers(128, 8192, 60)
+    t = 0.04 + 1e-4 * n + 2.4e-6 * L + rng.normal(0, 1e-3, 60)
+    assert np.allclose(m.predictor_fit_monotone(n, L, t), m.predictor_fit(n, L, t), rtol=1e-7, atol=1e-12)
+
+
+def pin_monotone_fit_clamps_and_refits(m):
+    """Steps whose time falls with the batch size (launch-bound, noisy): the slope on n_tokens would be
+    negative.  The constrained fit puts it at exactly 0 and the rest is the line in L_context alone."""
+    n = np.array([1, 1, 1, 1, 4, 4, 4, 4, 16, 16, 16, 16, 64, 64, 64, 64], float)
+    c = np.array([128, 1024, 4096, 8192] * 4, float)
+    L = n * c
+    t = 0.03 + 1.2e-6 * L - 3.2e-4 * n  # what a 16-point probe run once produced: b < 0
+    free = m.predictor_fit(n, L, t)
+    assert free[1] < 0
+    a, b, cc = m.predictor_fit_monotone(n, L, t)
+    assert b == 0.0 and cc > 0
+    slope, icpt = np.polyfit(L, t, 1)
+    assert a == pytest.approx(icpt, rel=1e-9) and cc == pytest.approx(slope, rel=1e-9)
+    _kkt((a, b, cc), n, L, t)
+    # both slopes negative: the mean
+    t2 = 5.0 - 1e-3 * n - 1e-7 * L
+    a, b, cc = m.predictor_fit_monotone(n, L, t2)
+    assert b == 0.0 and cc == 0.0 and a == pytest.approx(t2.mean(), rel=1e-12)
+
+
+def pin_monotone_fit_is_the_constrained_minimum(m):
+    rng = np.random.default_rng(6)
+    for trial in range(20):
+        n = rng.integers(1, 64, 16).astype(float)
+        L = n * rng.integers(128, 8192, 16)
+        t = 0.05 + rng.normal(0, 2e-4) * n + rng.normal(1e-6, 2e-6) * L + rng.normal(0, 5e-3, 16)
+        coef = np.array(m.predictor_fit_monotone(n, L, t))
+        _kkt(coef, n, L, t)
+        rss = lambda c: float(((c[0] + c[1] * n + c[2] * L - t) ** 2).sum())
+        best = rss(coef)
+        for _ in range(200):  # no feasible point nearby does better
+            d = rng.normal(0, 1, 3) * np.array([1e-3, 1e-5, 1e-8])
+            cand = coef + d
+            cand[1:] = np.maximum(cand[1:], 0.0)
+            assert rss(cand) >= best * (1 - 1e-12)
+
+
+PINS = [pin_monotone_fit_equals_ols_inside_the_region, pin_monotone_fit_clamps_and_refits,
+        pin_monotone_fit_is_the_constrained_minimum, pin_ols_by_hand, pin_exact_recovery_on_the_paper_grid, pin_residual_is_orthogonal_to_the_regressors,
         pin_mape_definition, pin_rolling_window_forgets_old_steps, pin_budget_formula, pin_worked_example,
         pin_feasible_and_maximal_against_brute_force, pin_no_slack_no_width_and_ample_slack_full_width,
         pin_equal_branches_closed_form, pin_cheapest_first_under_linear_utility, pin_table_utility_and_zero_gain_stops]
@@ -232,16 +294,18 @@ MUTANTS = {
     "slack_of_the_richest_request": ("min(r.slack_ms for r in requests)", "max(r.slack_ms for r in requests)"),
     "slack_only_of_requests_with_branches": ("min(r.slack_ms for r in requests)",
                                              "min(r.slack_ms for r in requests if r.branch_context)"),
-    "feasibility_on_increment_only": ("if t_w > budget:", "if t_w - t_step > budget:"),
-    "branch_priced_as_its_parent": ("L + r.branch_context[granted[i]]", "L + r.base_context"),
-    "always_first_branch_context": ("L + r.branch_context[granted[i]]", "L + r.branch_context[0]"),
-    "token_count_not_widened": ("n_w, L_w = n + 1, L", "n_w, L_w = n, L"),
-    "score_ignores_cost": ("score = du / (EPS + max(0.0, t_w - t_step))", "score = du"),
-    "score_ignores_utility": ("score = du / (EPS + max(0.0, t_w - t_step))", "score = 1.0 / (EPS + max(0.0, t_w - t_step))"),
-    "later_request_wins_ties": ("if best is None or score > best[0]:", "if best is None or score >= best[0]:"),
-    "pruned_request_comes_back": ("                continue  # pruned", "                still.append(i); continue  # pruned"),
-    "stops_one_branch_early": ("if granted[i] >= len(requests[i].branch_context):",
-                               "if granted[i] >= len(requests[i].branch_context) - 1:"),
+    "feasibility_on_increment_only": ("if priced[i] <= budget]", "if priced[i] - t_step <= budget]"),
+    "branch_priced_as_its_parent": ("step[1] + requests[i].branch_context[granted[i]]", "step[1] + requests[i].base_context"),
+    "always_first_branch_context": ("step[1] + requests[i].branch_context[granted[i]]", "step[1] + requests[i].branch_context[0]"),
+    "token_count_not_widened": ("return (step[0] + 1, step[1]", "return (step[0], step[1]"),
+    "score_ignores_cost": ("return gain / (EPS + max(0.0, t_widened - t_step))", "return gain"),
+    "score_ignores_utility": ("return gain / (EPS + max(0.0, t_widened - t_step))", "return 1.0 / (EPS + max(0.0, t_widened - t_step))"),
+    "later_request_wins_ties": ("chosen = feasible[ratios.index(top)]", "chosen = feasible[len(ratios) - 1 - ratios[::-1].index(top)]"),
+    "pruned_request_comes_back": ("considered = [i for i in feasible if granted[i]", "considered = [i for i in considered if granted[i]"),
+    "stops_one_branch_early": ("if granted[i] < len(requests[i].branch_context)]",
+                               "if granted[i] < len(requests[i].branch_context) - 1]"),
+    "monotone_fit_forgets_a_bound": ("bounds=([-np.inf, 0.0, 0.0]", "bounds=([-np.inf, -np.inf, 0.0]"),
+    "monotone_fit_bounds_the_intercept": ("bounds=([-np.inf, 0.0, 0.0]", "bounds=([0.0, 0.0, 0.0]"),
     "concave_is_linear": ("return lambda k: weight * math.log2(1.0 + k)", "return lambda k: weight * k"),
 }
 

@@ -48,6 +48,17 @@ def test_predictor_fitted_from_the_probe(ctx_qwen):
     assert predictor_mape(coef, n, L, t) == pytest.approx(mape, rel=1e-12)
     print(f"[predictor] a={coef[0]:.4f} ms b={coef[1]:.3e} c={coef[2]:.3e} MAPE {mape:.1f}%")
     assert coef[2] > 0  # more context costs more time
+    # what a refresh hands the planner: the fit under b, c >= 0 (16 noisy, partly launch-bound steps can give the
+    # plain fit a negative slope on the batch size, which the planner refuses)
+    mono, mono_mape = predictor_fit(n, L, t, monotone=True)
+    assert mono[1] >= 0 and mono[2] > 0
+    assert np.allclose(mono, ora.predictor_fit_monotone(n, L, t), rtol=1e-6, atol=1e-11)
+    if coef[1] >= 0:
+        assert np.allclose(mono, coef, rtol=1e-9, atol=1e-13)
+    from paper_2605_06914_amd import admit_step
+    granted, res = admit_step(mono, [1024, 1024], [1e3, 1e3], [[100, 100], []])
+    assert granted.tolist() == [2, 0]
+    print(f"[predictor, monotone] a={mono[0]:.4f} ms b={mono[1]:.3e} c={mono[2]:.3e} MAPE {mono_mape:.1f}%")
     # the largest step streams 2.1 GB per layer: its time is set by HBM, not by launch overheads
     assert t[-1] > 10 * t[0]
 
