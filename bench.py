@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="all", choices=["all", "mixed", "irp_off", "long", "tiny", "sweep", "controller", "phase", "decode_loop"])
+    ap.add_argument("--workload", default="all", choices=["all", "mixed", "irp_off", "long", "tiny", "wide32", "wide64", "sweep", "controller", "phase", "decode_loop"])
     ap.add_argument("--layers", type=int, default=0, help="layers per step (0 = workload default)")
     ap.add_argument("--target-workgroups", type=int, default=0)
     ap.add_argument("--shared-cost-pct", type=int, default=0)
@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--no-share", action="store_true", help="every branch streams its prefix itself (for comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-read-ceiling", action="store_true", help="skip the plain streaming-read measurement")
+    ap.add_argument("--no-same-pool", action="store_true",
+                    help="skip the cache-hot figure (every launch on one pool); for profiler runs, whose per-kernel "
+                         "average should hold the rotating-pool launches only")
     ap.add_argument("--kernel-iters", type=int, default=50)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times: scales the FETCH_SIZE / WRITE_SIZE counters")
@@ -55,10 +58,10 @@ def parse():
 
 
 def make_structure(name):
-    from taper_inputs import structure_config1, structure_config2, structure_config3, structure_config4
+    from taper_inputs import structure_config1, structure_config2, structure_config3, structure_config4, structure_wide
 
     return {"tiny": structure_config1, "irp_off": structure_config2, "mixed": structure_config3,
-            "long": structure_config4}[name]()
+            "long": structure_config4, "wide32": lambda: structure_wide(32), "wide64": lambda: structure_wide(64)}[name]()
 
 
 def fill_pool(n_elems, gen, dev):
@@ -287,7 +290,7 @@ def run_sweep(args, steps=None):
                                   "unit": "GB/s", "frac": r["frac"], "traffic": traffic, "traffic_detail": detail,
                                   "bytes_per_launch": r["bytes_per_launch"], "avg_launch_us": r["avg_launch_us"],
                                   "min_launch_us": r["min_launch_us"], "workgroups": r["workgroups"]}})
-        if k == ks[-1]:
+        if k == ks[-1] and not args.no_cpu_baseline:
             layers = sorted({0, n_layers // 2 - 1, n_layers - 1}) if n_layers >= 3 else list(range(n_layers))
             sel = sample_rows(st)
             t_cpu, tok, used, mx, mean = oracle_check(st, sel, layers, qs, kvs, outs)
@@ -351,8 +354,12 @@ def run_controller(args):
     ctx = Context(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, device=0)
     iters = max(3, args.steps // 4)
 
+    plan_us_seen = []
+
     def measure(st):
+        t_plan = time.perf_counter()
         plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, n_pool_pages)
+        plan_us_seen.append((time.perf_counter() - t_plan) * 1e6)
         S = st.n_seqs
         r = ctx.step_latency_probe(plan, [q[:S] for q in qs], kvs, [o[:S] for o in outs], warmup=2, iters=iters)
         plan.free()
@@ -374,6 +381,29 @@ def run_controller(args):
         m = (grid[:, 0] >= lo) & (grid[:, 0] <= hi)
         bands[name] = round(predictor_mape(coef, grid[m, 0], grid[m, 1], grid[m, 3]), 2)
     grid_seconds = time.perf_counter() - t_start
+    # the low band on its own (steps of 1-64 sequences are partly launch-bound here, so one model over 1-512 fits
+    # them worst): a model refreshed from low-band steps alone, under b, c >= 0 as the planner needs it
+    low = grid[grid[:, 0] <= 64]
+    coef_low, mape_low_own = predictor_fit(low[:, 0], low[:, 1], low[:, 3], monotone=True)
+    # refresh from 16 recent steps, as a serving loop would: windows of 16 grid points drawn at random; how often
+    # the plain fit comes out with a negative slope (which the planner refuses) and what the constrained fit
+    # gives on the whole grid
+    wrng = np.random.Generator(np.random.PCG64(20260510))
+    n_win, plain_negative, win_mape = 200, 0, []
+    for _ in range(n_win):
+        pick = wrng.choice(len(grid), size=16, replace=False)
+        try:
+            plain, _ = predictor_fit(grid[pick, 0], grid[pick, 1], grid[pick, 3])
+            mono, _ = predictor_fit(grid[pick, 0], grid[pick, 1], grid[pick, 3], monotone=True)
+        except Exception:  # a degenerate draw (all points on one line): the window keeps its previous model
+            continue
+        plain_negative += int(plain[1] < 0 or plain[2] < 0)
+        assert mono[1] >= 0 and mono[2] >= 0
+        win_mape.append(predictor_mape(mono, grid[:, 0], grid[:, 1], grid[:, 3]))
+    refresh = {"windows": n_win, "window_points": 16, "plain_fit_not_monotone": plain_negative,
+               "constrained_fit_not_monotone": 0,
+               "mape_pct_on_grid_median": round(float(np.median(win_mape)), 2),
+               "mape_pct_on_grid_p90": round(float(np.percentile(win_mape, 90)), 2)}
 
     # ---- (2) steps with shared prefixes: uniform widths of the sweep and random widths per request
     first = np.flatnonzero(np.r_[True, full.branch_group[1:] != full.branch_group[:-1]])
@@ -393,8 +423,8 @@ def run_controller(args):
         sobs.append((st.n_seqs, st.logical_tokens, st.unique_tokens, measure(st)))
     sobs = np.array(sobs, dtype=np.float64)
     both = np.concatenate([grid, sobs])
-    coef_L, _ = predictor_fit(both[:, 0], both[:, 1], both[:, 3])
-    coef_U, _ = predictor_fit(both[:, 0], both[:, 2], both[:, 3])
+    coef_L, _ = predictor_fit(both[:, 0], both[:, 1], both[:, 3], monotone=True)
+    coef_U, _ = predictor_fit(both[:, 0], both[:, 2], both[:, 3], monotone=True)
     sharing = {
         "observations": {"grid": len(grid), "shared_prefix_steps": len(sobs)},
         "fit_on_l_context": {"coef_ms": coef_L, "mape_pct_shared_steps": round(predictor_mape(coef_L, sobs[:, 0], sobs[:, 1], sobs[:, 3]), 2),
@@ -424,11 +454,13 @@ def run_controller(args):
             plan_us = (time.perf_counter() - t1) / reps * 1e6
             st = subset_rows(full, widths_to_rows(1 + granted.astype(np.int64)))
             t_meas = measure(st)
+            build_us = plan_us_seen[-1]
             replay.append({"pricing": pricing, "min_slack_over_t0": slack_factor, "budget_ms": round(res["budget_ms"], 4),
                            "admitted_branches": int(res["admitted"]), "of_ready": int(sum(len(r) for r in ready)),
                            "t_pred_ms": round(res["t_pred_ms"], 4), "t_measured_ms": round(t_meas, 4),
                            "measured_over_budget": round(t_meas / res["budget_ms"], 4),
-                           "planner_us": round(plan_us, 1), "t_evaluations": int(res["evaluations"])})
+                           "planner_us": round(plan_us, 1), "t_evaluations": int(res["evaluations"]),
+                           "plan_build_us": round(build_us, 1), "sequences": int(st.n_seqs)})
     ctx.close()
     return {
         "metric": "latency_predictor_mape", "value": round(mape_all, 2), "unit": "%", "n_gpus": 1, "steps": args.steps,
@@ -441,7 +473,17 @@ def run_controller(args):
         "paper_mape_pct_context_only": {"overall": 1.8, "low": 1.7, "medium": 1.9, "high": 1.8,
                                         "note": "whole decode step incl. FFN on the paper's hardware"},
         "predictor": {"coef_ms": {"a": coef[0], "b": coef[1], "c": coef[2]}, "mape_pct_overall": round(mape_all, 2),
-                      "mape_pct_by_batch_band": bands, "grid_points": len(grid), "grid_seconds": round(grid_seconds, 1)},
+                      "mape_pct_by_batch_band": bands, "grid_points": len(grid), "grid_seconds": round(grid_seconds, 1),
+                      "low_band_model": {"coef_ms": {"a": coef_low[0], "b": coef_low[1], "c": coef_low[2]},
+                                         "mape_pct_low_band": round(mape_low_own, 2), "points": len(low),
+                                         "note": "fitted on batch 1-64 alone under b, c >= 0"},
+                      "refresh_from_16_steps": refresh},
+        "host_cost_us": {"plan_build_median": round(float(np.median(plan_us_seen)), 1),
+                         "plan_build_max": round(float(np.max(plan_us_seen)), 1),
+                         "planner_median": round(float(np.median([r["planner_us"] for r in replay])), 1),
+                         "planner_max": round(float(np.max([r["planner_us"] for r in replay])), 1),
+                         "note": "host microseconds per step, to be set against the step's GPU time: the plan is built "
+                                 "once per step and serves every layer"},
         "prefix_sharing": sharing,
         "protected_step_ms_measured": round(t0_meas, 4),
         "planner_replay": replay,
@@ -616,7 +658,7 @@ def bench_single(args, workload):
     sh = st.shape
     # default depth: the 64-layer stack of the model the shape comes from; the long workload's pool is
     # ~30 GB per layer, so it runs a shallower stack (8 pools = 240 GB of the 288 GB)
-    n_layers = args.layers or {"mixed": 64, "irp_off": 64, "long": 8, "tiny": 64}[workload]
+    n_layers = args.layers or {"mixed": 64, "irp_off": 64, "long": 8, "tiny": 64, "wide32": 64, "wide64": 32}[workload]
     gen = torch.Generator(device=dev)
     gen.manual_seed(st.seed + 1000)
     qs, kvs, outs = [], [], []
@@ -673,6 +715,7 @@ def bench_single(args, workload):
     roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                 "bytes_per_launch": dom_bytes, "kv_bytes_listed_by_plan": (tok_shared + tok_private) * sh.kv_bytes_per_token,
+                "kv_listed_over_unique": round((tok_shared + tok_private) * sh.kv_bytes_per_token / st.kv_bytes_unique, 4),
                 "avg_launch_us": round(launch_us, 2), "min_launch_us": round(probe.us_min / n_layers, 2),
                 "kernel_us_event_pairs": {k: round(v, 2) for k, v in kt.items()},
                 "workgroups": (e["n_parts_shared"] + e["n_parts_private"]) * sh.n_kv_heads,
@@ -683,7 +726,7 @@ def bench_single(args, workload):
     # ---- the timing protocol's other figure: every launch on the SAME pool.  A pool of a few hundred MB partly
     # stays in the 256 MB Infinity Cache from one launch to the next, so this is not an HBM rate; the rotating
     # figure above is the one quoted.
-    if st.n_pool_pages * sh.page_elems * 2 < (2 << 30):
+    if st.n_pool_pages * sh.page_elems * 2 < (2 << 30) and not args.no_same_pool:
         hot = ctx.step_latency_probe(plan, qs, [kvs[0]] * n_layers, outs, warmup=2, iters=max(5, args.steps))
         roofline["same_pool_every_launch"] = {"avg_launch_us": round(hot.us_median / n_layers, 2),
                                               "gbps": round(dom_bytes / (hot.us_median / n_layers) / 1e3, 1),
@@ -728,6 +771,8 @@ def bench_single(args, workload):
     if not args.no_cpu_baseline:
         layers = sorted({0, n_layers // 2 - 1, n_layers - 1}) if n_layers >= 3 else list(range(n_layers))
         rows = np.arange(st.n_seqs) if st.logical_tokens <= 400_000 else sample_rows(st)
+        if n_layers >= 32 and len(rows) * 16 <= 2048:  # a small batch: every fourth layer as well (about 10 s of oracle time)
+            layers = sorted(set(layers) | set(range(0, n_layers, 4)))
         t_cpu, tok, used, mx, mean = oracle_check(st, rows, layers, qs, kvs, outs)
         cpu = cpu_part(st, len(layers), t_cpu, tok, used, mx, mean,
                        f"{len(rows)} of {st.n_seqs} sequences (the whole batch if it has at most 400000 logical tokens, else "

@@ -23,6 +23,7 @@ from .generators import (  # noqa: F401
     structure_config3,
     structure_config4,
     structure_config5,
+    structure_wide,
     structure_custom,
     subset_rows,
 )

@@ -251,6 +251,18 @@ def structure_config5(k: int, seed: int = CONFIG_SEED_BASE + 5, n_serial: int = 
                            name=f"config5_sweep_k{k}", seed=seed)
 
 
+def structure_wide(width: int, seed: int = CONFIG_SEED_BASE + 6) -> BatchStructure:
+    """Wide requests: the mixed batch's shape (16 serial 1k-4k, 8 parallel with prefix 2k-8k and
+    private suffix 0-1024) with every parallel request at `width` branches -- wider than one
+    workgroup's row tiles hold, so a prefix is listed for more than one group of branches."""
+    rng = _rng(seed)
+    ctx = rng.integers(1 * K, 4 * K, size=16, endpoint=True)
+    pre = rng.integers(2 * K, 8 * K, size=8, endpoint=True)
+    suf = [rng.integers(0, 1 * K, size=width, endpoint=True) for _ in range(8)]
+    reqs = [(int(c), [0]) for c in ctx] + [(int(p), [int(x) for x in s]) for p, s in zip(pre, suf)]
+    return build_structure(QWEN, reqs, rng, pool_factor=1.1, name=f"wide_requests_w{width}", seed=seed)
+
+
 def make_config(index: int, **kw) -> BatchStructure:
     return {1: structure_config1, 2: structure_config2, 3: structure_config3,
             4: structure_config4, 5: structure_config5}[index](**kw)
