@@ -182,6 +182,11 @@ typedef struct {
                                   launch ends evenly.  -1 = none; values above 90 count as 90    */
     int32_t pool_item_tokens;  /* size of the pool's items, rounded down to a multiple of 32 tokens (at
                                   least 32); 0 = default: a quarter of a share, between 512 and 1536 */
+    int32_t scatter_sub_groups; /* 0 = default: the sub-groups of a request wider than
+                                  max_branches_per_item get the same cuts, a share per item and
+                                  neighbouring workgroups, so that they stream the prefix in step
+                                  and share it in the L2; 1 = they are placed like unrelated
+                                  requests, one after the other                               */
 } taper_plan_options;
 
 TAPER_API int taper_create(const taper_attn_config *cfg /* host */, taper_ctx **out_ctx);

@@ -54,6 +54,7 @@ struct Segment {
     int32_t seq0, n_branch, page0, n_tokens, kind;
     int32_t ends_seq = 0;  // private: the last tokens of its sequence in plan order (whoever streams them usually merges)
     int32_t whole_seq = 0;  // private: the sequence's whole context
+    int32_t siblings = 0;   // shared: this and the next siblings - 1 segments stream the same prefix (one request, cut into sub-groups)
 };
 
 // Cost model of a workgroup share, in units of one private token's streaming time: an item of
@@ -155,7 +156,31 @@ int partition_even(const std::vector<Segment>& segs, int64_t quota, int blk, con
         if (fill > 0) ++part;
         fill = 0;
     };
-    for (const Segment& s : segs) {
+    for (size_t si = 0; si < segs.size(); ++si) {
+        const Segment& s = segs[si];
+        if (s.siblings >= 2) {
+            // Sub-groups of one request read the same pages.  They get the same cuts, every item a share of its
+            // own and therefore the launch's start as its start, in workgroups next to each other: the sub-groups
+            // then stream the prefix in step, and what the first one fetched is still in the L2 of the XCD (one
+            // per kv head) when the others ask for it.  Shares that come out short take from the pool.
+            close();
+            const int64_t blocks = (s.n_tokens + blk - 1) / blk;
+            const int64_t spread = blocks + tail_discount;
+            const int64_t k = blocks <= cap + min_blocks / 2 ? 1 : std::max<int64_t>(1, (spread + cap - 1) / cap);
+            int64_t remaining = blocks, off = 0;
+            for (int64_t i = 0; i < k; ++i) {
+                int64_t take = spread / k + (i < spread % k ? 1 : 0);
+                take = i + 1 < k ? std::max<int64_t>(1, std::min(take, remaining - (k - 1 - i))) : remaining;
+                for (int j = 0; j < s.siblings; ++j) {
+                    emit(segs[si + j], off, take);
+                    close();
+                }
+                off += take;
+                remaining -= take;
+            }
+            si += s.siblings - 1;
+            continue;
+        }
         int64_t remaining = (s.n_tokens + blk - 1) / blk, off = 0;  // blocks
         int64_t room = (quota - fill - cost.fixed) / blk_cost;      // blocks that still fit the current share
         if (fill > 0 && room < remaining && room < min_blocks) {    // not worth an item: start the next share
@@ -347,6 +372,7 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
         if (pl > 0) {
             if (B >= 2 && share_prefix) {
                 const int n_sub = (B + cap_branches - 1) / cap_branches;
+                const size_t first = shared.size();
                 for (int k = 0; k < n_sub; ++k) {  // balanced sub-groups of at most cap_branches
                     const int lo = a + (int)((int64_t)B * k / n_sub), hi = a + (int)((int64_t)B * (k + 1) / n_sub);
                     if (hi - lo >= 2)
@@ -354,6 +380,7 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
                     else if (hi - lo == 1)
                         priv.push_back({lo, 1, 0, pl, 1});
                 }
+                if (shared.size() - first >= 2 && !(opts && opts->scatter_sub_groups)) shared[first].siblings = (int32_t)(shared.size() - first);
             } else {
                 for (int s = a; s < b; ++s) priv.push_back({s, 1, 0, pl, 1});
             }

@@ -53,6 +53,8 @@ def random_case(seed, shape):
         opts["shared_item_cost"] = int(rng.choice([1, 5000]))
     if rng.random() < 0.2:
         opts["share_prefix"] = 0
+    if rng.random() < 0.25:
+        opts["scatter_sub_groups"] = 1
     return seg, opts
 
 

@@ -164,7 +164,7 @@ def test_plan_integers_match_oracle(maker):
 
 
 @pytest.mark.parametrize("kw", [dict(share_prefix=False), dict(target_workgroups=8), dict(target_workgroups=100000), dict(target_workgroups=100000, min_share_tokens=1),
-                                dict(max_branches_per_item=3), dict(pool_pct=-1), dict(pool_pct=90, pool_item_tokens=64), dict(pool_pct=100, pool_item_tokens=200),
+                                dict(max_branches_per_item=3), dict(scatter_sub_groups=True), dict(max_branches_per_item=4, scatter_sub_groups=True), dict(pool_pct=-1), dict(pool_pct=90, pool_item_tokens=64), dict(pool_pct=100, pool_item_tokens=200),
                                 dict(shared_cost_pct=300, shared_item_cost=5000, private_item_cost=1)])
 def test_plan_options(kw):
     reqs = [(37, [0]), (50, [0, 7, 16, 21]), (16, [1]), (700, [0, 33, 64, 65, 129, 300]), (1, [0]), (0, [45]),
@@ -192,3 +192,33 @@ def test_config4_plan_is_balanced():
     assert nsh > 0 and (nsh + e["n_parts_private"]) * 8 <= 600
     for t in (tok[:nsh], tok[nsh:]):
         assert t.max() <= 1.25 * t.sum() / len(t) + 64
+
+
+@pytest.mark.parametrize("width,target", [(32, 0), (64, 0), (64, 4096), (100, 64)])
+def test_sub_groups_of_a_wide_request_stream_the_prefix_side_by_side(width, target):
+    """A request wider than one item is cut into sub-groups that each read the whole prefix.  Their items
+    have the same cuts, a share each, and neighbouring shares (workgroups that start together and, for one
+    kv head, sit on one XCD), chunk by chunk; with scatter_sub_groups they are placed like unrelated requests."""
+    from taper_inputs import structure_wide
+
+    st = structure_wide(width) if width <= 64 else structure_custom(QWEN, [(900, [0]), (5000, [7] * width), (70, [1, 2])], seed=3)
+    e = check_plan_against_oracle(st, target_workgroups=target)
+    F = {n: i for i, n in enumerate(e["item_fields"])}
+    items, ps = e["items"], e["part_start"]
+    shared = items[items[:, F["kind"]] == 0]
+    sizes = np.bincount(st.branch_group)
+    first = np.concatenate([[0], np.cumsum(sizes)[:-1]])
+    checked = 0
+    for g in np.flatnonzero(sizes > 24):
+        mine = shared[(shared[:, F["seq0"]] >= first[g]) & (shared[:, F["seq0"]] < first[g] + sizes[g])]
+        n_sub = -(-int(sizes[g]) // 24)
+        assert len(mine) % n_sub == 0 and len(np.unique(mine[:, F["seq0"]])) == n_sub
+        parts = mine[:, F["part"]]
+        assert np.array_equal(parts, parts[0] + np.arange(len(mine))), "neighbouring shares, in order"
+        assert np.all(np.diff(ps)[parts] == 1), "a share each"
+        for c in range(len(mine) // n_sub):  # chunk c of every sub-group: the same pages
+            chunk = mine[c * n_sub : (c + 1) * n_sub]
+            assert len(set(chunk[:, F["page0"]])) == 1 and len(set(chunk[:, F["n_tokens"]])) == 1
+            assert sorted(chunk[:, F["seq0"]]) == sorted(np.unique(mine[:, F["seq0"]]))
+        checked += 1
+    assert checked >= 1
