@@ -76,11 +76,13 @@ def fill_pool(n_elems, gen, dev):
 
 
 def kernels_source_sha16():
-    """Which kernel source a stored counter profile belongs to."""
+    """Which sources a stored counter profile belongs to: the kernels and the plan that feeds them."""
     import hashlib
 
-    src = os.path.join(ROOT, "paper_2605_06914_amd", "csrc", "taper_kernels.hip")
-    return hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    h = hashlib.sha256()
+    for name in ("taper_kernels.hip", "taper_plan.cpp"):
+        h.update(open(os.path.join(ROOT, "paper_2605_06914_amd", "csrc", name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def stored_traffic(key):
