@@ -283,7 +283,7 @@ def run_sweep(args, steps=None):
     for k, st in sts.items():
         S = st.n_seqs
         qs, outs = [q[:S] for q in qs_all], [o[:S] for o in outs_all]
-        r = measure(ctx, st, qs, kvs, outs, steps, 1, {})
+        r = measure(ctx, st, qs, kvs, outs, steps, 1, json.loads(args.plan_options))
         traffic, detail = stored_traffic(f"sweep_k{k}")
         rows.append({"k": k, "admitted_branches": 32 * k, "n_seqs": S, "l_context": st.logical_tokens,
                      "tokens_unique": st.unique_tokens, "ms_per_step": r["ms_per_step"],

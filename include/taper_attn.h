@@ -182,6 +182,11 @@ typedef struct {
                                   launch ends evenly.  -1 = none; values above 90 count as 90    */
     int32_t pool_item_tokens;  /* size of the pool's items, rounded down to a multiple of 32 tokens (at
                                   least 32); 0 = default: a quarter of a share, between 512 and 1536 */
+    int32_t small_step_grid;   /* 0 = default: when target_workgroups is 0, a step without shared-prefix work
+                                  is cut for one workgroup per compute unit instead of two if that cuts
+                                  sequences into so many fewer pieces that it pays (each piece costs
+                                  partial rows and a share of a merge); 1 = the same rule for an explicit
+                                  target_workgroups (then halved); -1 = never                    */
     int32_t scatter_sub_groups; /* 0 = default: the sub-groups of a request wider than
                                   max_branches_per_item get the same cuts, a share per item and
                                   neighbouring workgroups, so that they stream the prefix in step

@@ -68,7 +68,7 @@ class taper_plan_options(ctypes.Structure):
                 ("shared_item_cost", ctypes.c_int32), ("private_item_cost", ctypes.c_int32),
                 ("private_merge_cost", ctypes.c_int32), ("solo_item_tokens", ctypes.c_int32),
                 ("min_share_tokens", ctypes.c_int32), ("pool_pct", ctypes.c_int32), ("pool_item_tokens", ctypes.c_int32),
-                ("scatter_sub_groups", ctypes.c_int32)]
+                ("small_step_grid", ctypes.c_int32), ("scatter_sub_groups", ctypes.c_int32)]
 
 
 class taper_probe_result(ctypes.Structure):
@@ -296,14 +296,14 @@ class Context:
                    target_workgroups: int = 0, share_prefix: bool = True, max_branches_per_item: int = 0,
                    shared_cost_pct: int = 0, shared_item_cost: int = 0, private_item_cost: int = 0,
                    pool_pct: int = 0, pool_item_tokens: int = 0, private_merge_cost: int = 0, solo_item_tokens: int = 0,
-                   min_share_tokens: int = 0, scatter_sub_groups: bool = False, stream=None) -> Plan:
+                   min_share_tokens: int = 0, scatter_sub_groups: bool = False, small_step_grid: int = 0, stream=None) -> Plan:
         bt = _i32(block_table)
         grp, pl, sl = _i32(branch_group), _i32(prefix_len), _i32(suffix_len)
         if bt.ndim != 2 or not (len(grp) == len(pl) == len(sl) == bt.shape[0]):
             raise TaperError(TAPER_EINVAL, "block_table must be [S, max_blocks] and the per-sequence arrays length S")
         opts = taper_plan_options(target_workgroups, int(share_prefix), max_branches_per_item, shared_cost_pct,
                                   shared_item_cost, private_item_cost, private_merge_cost, solo_item_tokens,
-                                  min_share_tokens, pool_pct, pool_item_tokens, int(scatter_sub_groups))
+                                  min_share_tokens, pool_pct, pool_item_tokens, small_step_grid, int(scatter_sub_groups))
         h = ctypes.c_void_p()
         st = 0 if self.cfg.device < 0 else _stream(stream)
         _check(load_library().taper_plan_build(self._h, bt.shape[0], bt.ctypes.data, bt.shape[1], grp.ctypes.data,
@@ -320,7 +320,7 @@ class Context:
             raise TaperError(TAPER_EINVAL, "block_table must be [S, max_blocks], seg_start length S + 1 ending at len(seg_len)")
         names = ["target_workgroups", "share_prefix", "max_branches_per_item", "shared_cost_pct", "shared_item_cost",
                  "private_item_cost", "private_merge_cost", "solo_item_tokens", "min_share_tokens", "pool_pct",
-                 "pool_item_tokens", "scatter_sub_groups"]
+                 "pool_item_tokens", "small_step_grid", "scatter_sub_groups"]
         vals = {n: 0 for n in names}
         vals["share_prefix"] = 1
         for k, v in options.items():

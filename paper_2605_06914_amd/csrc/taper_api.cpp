@@ -483,6 +483,7 @@ int taper_plan_build_segments(taper_ctx* ctx, int n_seqs, const int32_t* block_t
     std::memset(&o, 0, sizeof o);
     o.share_prefix = 1;
     if (opts) o = *opts;
+    if (o.small_step_grid == 0) o.small_step_grid = o.target_workgroups <= 0 ? 1 : -1;  // the rule is for grids left to the library
     if (o.target_workgroups <= 0) o.target_workgroups = ctx->default_workgroups;  // (0 on a host-only context: 512)
     int st = taper::build_host_plan_segments(ctx->cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len,
                                              seg_start, seg_len, n_pool_pages, &o, &plan->host, &err);
@@ -633,6 +634,7 @@ int taper_decode_step_attention_static(taper_ctx* ctx, int n_seqs, const void* q
     std::memset(&o, 0, sizeof o);
     o.share_prefix = 1;
     o.target_workgroups = ctx->default_workgroups;
+    o.small_step_grid = 1;
     int st = taper::build_host_plan(ctx->cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len, suffix_len,
                                     n_pool_pages, &o, &h, &err);
     if (st != TAPER_OK) return fail(st, err);

@@ -50,6 +50,9 @@ int validate_config(const taper_attn_config& cfg, std::string* err) {
 
 namespace {
 
+constexpr int64_t kPieceCostTokens = 200;   // what one more piece of a cut sequence costs, in tokens' streaming time
+constexpr int64_t kOnePerUnitLossPct = 3;   // what one workgroup per compute unit instead of two costs, percent
+
 struct Segment {
     int32_t seq0, n_branch, page0, n_tokens, kind;
     int32_t ends_seq = 0;  // private: the last tokens of its sequence in plan order (whoever streams them usually merges)
@@ -228,10 +231,10 @@ int build_host_plan(const taper_attn_config& cfg, int n_seqs, const int32_t* blo
                                     suffix_len, n_pool_pages, opts, out, err);
 }
 
-int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int32_t* block_table, int bt_row_stride,
-                             const int32_t* branch_group, const int32_t* prefix_len, const int32_t* seg_start,
-                             const int32_t* seg_len, int64_t n_pool_pages, const taper_plan_options* opts,
-                             HostPlan* out, std::string* err) {
+static int build_for_grid(const taper_attn_config& cfg, int n_seqs, const int32_t* block_table, int bt_row_stride,
+                          const int32_t* branch_group, const int32_t* prefix_len, const int32_t* seg_start,
+                          const int32_t* seg_len, int64_t n_pool_pages, const taper_plan_options* opts,
+                          HostPlan* out, std::string* err) {
     int st = validate_config(cfg, err);
     if (st != TAPER_OK) return st;
     if (!block_table || !branch_group || !prefix_len || !seg_start || !out) {
@@ -541,6 +544,40 @@ int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int
         }
     }
     return TAPER_OK;
+}
+
+// Cutting a sequence costs: every piece writes partial rows, announces them, and one workgroup reads them all back
+// (three dependent trips through a loaded memory system, some 200 tokens' streaming time per piece).  A step
+// without shared-prefix work whose shares are short is therefore also cut for half the grid -- one workgroup per
+// compute unit instead of two, which alone reads 1 to 4 % slower -- and that plan is taken when it saves enough
+// pieces to pay for it.  (32 requests of 1024-4096 tokens: 86 pieces become 54 and the launch 2.5 % faster;
+// 32 equal requests: no piece at all, 5-10 % faster; a large step has few pieces per share either way.)
+int build_host_plan_segments(const taper_attn_config& cfg, int n_seqs, const int32_t* block_table, int bt_row_stride,
+                             const int32_t* branch_group, const int32_t* prefix_len, const int32_t* seg_start,
+                             const int32_t* seg_len, int64_t n_pool_pages, const taper_plan_options* opts,
+                             HostPlan* out, std::string* err) {
+    int st = build_for_grid(cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len, seg_start, seg_len,
+                            n_pool_pages, opts, out, err);
+    if (st != TAPER_OK || !opts || opts->small_step_grid <= 0) return st;
+    const int grid = opts->target_workgroups > 0 ? opts->target_workgroups : 512;
+    const int parts_full = std::max(1, grid / cfg.n_kv_heads);
+    if (out->n_parts_shared != 0 || out->n_pool_items != 0 || out->n_parts_private < parts_full || parts_full < 2) return st;
+    auto pieces = [](const HostPlan& h) {
+        int64_t n = 0;
+        for (const taper_work_item& it : h.items) n += it.kind == 1;
+        return n;
+    };
+    const int64_t pieces_full = pieces(*out);
+    if (pieces_full * kPieceCostTokens * 100 <= out->tokens_unique * kOnePerUnitLossPct) return st;  // cannot pay even if all went
+    taper_plan_options half = *opts;
+    half.target_workgroups = grid / 2;
+    HostPlan alt;
+    std::string err2;
+    if (build_for_grid(cfg, n_seqs, block_table, bt_row_stride, branch_group, prefix_len, seg_start, seg_len, n_pool_pages,
+                       &half, &alt, &err2) != TAPER_OK)
+        return st;
+    if ((pieces_full - pieces(alt)) * kPieceCostTokens * 100 > out->tokens_unique * kOnePerUnitLossPct) *out = std::move(alt);
+    return st;
 }
 
 void resolve_slots_host(const HostPlan& p, int P, int64_t* slots, int64_t stride) {

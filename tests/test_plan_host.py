@@ -222,3 +222,32 @@ def test_sub_groups_of_a_wide_request_stream_the_prefix_side_by_side(width, targ
             assert sorted(chunk[:, F["seq0"]]) == sorted(np.unique(mine[:, F["seq0"]]))
         checked += 1
     assert checked >= 1
+
+
+def test_small_steps_without_shared_work_take_half_the_grid_when_that_saves_pieces():
+    """With the grid left to the library, a step of serial requests is cut for one workgroup per compute unit
+    instead of two when that cuts sequences into so many fewer pieces that it pays; never with shared-prefix
+    work, never for an explicit grid (unless asked), never when nothing is saved; the plan is a full cover
+    either way."""
+    F = None
+
+    def pieces(e):
+        nonlocal F
+        F = {n: i for i, n in enumerate(e["item_fields"])}
+        return int((e["items"][:, F["kind"]] == 1).sum())
+
+    irp = structure_config2()
+    auto, never, explicit = (check_plan_against_oracle(irp, **kw) for kw in ({}, dict(small_step_grid=-1), dict(target_workgroups=512)))
+    assert never["n_parts_private"] == explicit["n_parts_private"] == 64 and auto["n_parts_private"] == 32
+    assert pieces(auto) < pieces(never) == pieces(explicit)
+    asked = check_plan_against_oracle(irp, target_workgroups=512, small_step_grid=1)
+    assert asked["n_parts_private"] == 32
+    equal = structure_custom(QWEN, [(1024, [0])] * 32, seed=1)  # 256 (sequence, kv head) pairs: a workgroup each, nothing cut
+    e = check_plan_against_oracle(equal)
+    assert e["n_parts_private"] == 32 and pieces(e) == 0
+    uncut = structure_custom(QWEN, [(1024, [0])] * 128, seed=1)  # nothing is cut at the full grid: nothing to save
+    assert check_plan_against_oracle(uncut)["n_parts_private"] == 64
+    big = structure_config5(k=0)  # long shares: the pieces saved do not pay for the slower grid
+    assert check_plan_against_oracle(big)["n_parts_private"] == 64
+    mixed = check_plan_against_oracle(structure_config3())
+    assert mixed["n_parts_shared"] + mixed["n_parts_private"] == 64
