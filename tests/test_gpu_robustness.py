@@ -150,3 +150,40 @@ def test_reserve_then_no_growth():
     got, _, _ = run_gpu(ctx, b)
     assert_parity(got, ref, "after reserve")
     ctx.close()
+
+
+def test_two_batches_taking_turns_repeat_their_bits():
+    """Two different batches, finely cut (thousands of partial rows each, the same workspace), launched in
+    turns without a host synchronisation between the launches, 150 times each: every result must be the bits
+    of the first.  The partial rows, statistics and counters of one launch are what the next one finds in the
+    workspace; a merge that ran ahead of a writer, a counter that did not return to zero or a row picked up
+    from the other batch would change bits sooner or later."""
+    import torch
+
+    ctx = new_ctx()
+    batches = [fill_values_numpy(structure_custom(QWEN, POOL_REQS, seed=611)),
+               fill_values_numpy(structure_custom(QWEN, [(1800, [9, 0, 40, 77, 5]), (2500, [0]), (640, [3, 700]), (90, [0]),
+                                                         (1300, [1] * 11)], seed=612))]
+    dev = []
+    for b in batches:
+        st = b.structure
+        plan = ctx.plan_build(st.block_table, st.branch_group, st.prefix_len, st.suffix_len, st.n_pool_pages, **FINE)
+        q, kv = torch_bf16(b.q), torch_bf16(b.kv)
+        first = torch.full_like(q, float("nan"))
+        ctx.decode_step_attention(plan, q, kv, first)
+        torch.cuda.synchronize()
+        ref, _ = run_oracle(b)
+        assert_parity(f32_from_bf16_bits(bits_from_torch(first)).astype(np.float64), ref, "first launch")
+        dev.append((plan, q, kv, first, [torch.empty_like(q) for _ in range(6)]))
+    assert dev[0][0].export()["workspace_id"] == dev[1][0].export()["workspace_id"]
+    for rnd in range(25):
+        for k in range(6):  # 12 launches in a row on the stream, then compare
+            for plan, q, kv, _, outs in dev:
+                ctx.decode_step_attention(plan, q, kv, outs[k])
+        torch.cuda.synchronize()
+        for which, (_, _, _, first, outs) in enumerate(dev):
+            for k in range(6):
+                assert torch.equal(outs[k].view(torch.int16), first.view(torch.int16)), f"round {rnd}, launch {k}, batch {which}"
+    for plan, *_ in dev:
+        plan.free()
+    ctx.close()
