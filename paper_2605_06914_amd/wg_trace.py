@@ -9,8 +9,8 @@ workgroups with each other, not launches with the bench.
 
     python -m paper_2605_06914_amd.wg_trace mixed irp_off long k4 [--kw '{"pool_pct": 40}'] [--verbose]
 
-Workloads: mixed, irp_off, long, k<K> (admission sweep at width 1+K), b<N>x<C> (N serial
-requests of C tokens).  Needs a GPU; build the trace library first (on the CPU):
+Workloads: mixed, irp_off, long, k<K> (admission sweep at width 1+K), w<N> (the mixed shape with
+N branches per parallel request), b<N>x<C> (N serial requests of C tokens).  Needs a GPU; build the trace library first (on the CPU):
     python paper_2605_06914_amd/build.py --trace
 """
 from __future__ import annotations
@@ -41,6 +41,10 @@ def structure(name):
         return structure_config4()
     if name.startswith("k"):
         return structure_config5(int(name[1:]))
+    if name.startswith("w"):
+        from taper_inputs import structure_wide
+
+        return structure_wide(int(name[1:]))
     if name.startswith("b"):
         n, c = name[1:].split("x")
         return structure_custom(QWEN, [(int(c), [0])] * int(n), seed=1)
