@@ -19,6 +19,8 @@
 // chunks of a sequence (m, l in fp32; O / l in fp32 or, by default, in half precision with a
 // per-row power-of-two scale) are combined through their (m, l) by the workgroup that delivers
 // the sequence's last partial (merge_rows).
+#include <type_traits>
+
 #include "taper_internal.h"
 
 namespace taper {
@@ -402,7 +404,12 @@ struct PrivateSmem {
 // SOLO: the item is run by the calling wave alone (short sequences that are a single item:
 // four of them proceed side by side in a workgroup, with no barrier and no LDS); otherwise the
 // four waves of the workgroup share the item's blocks.
-template <int D, bool SOLO, int PF>
+// SB: the block-table row is read through the constant address space from a pointer the compiler knows to
+// be the same in all lanes.  Its entries then come by scalar loads, which do not wait for the KV loads in
+// flight (a vector load of a page id completes in order, behind everything issued before it: one block in
+// flight per wave).  That deeper pipeline pays on steps without shared-prefix work; next to shared-prefix
+// workgroups it takes bandwidth from them, and those launches keep the vector loads.
+template <int D, bool SOLO, int PF, bool SB>
 DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem<D>& sm) {
     constexpr int KS = D / 32, DT = D / 16, TILE = 16 * D;
     auto& sm_o = sm.o;
@@ -417,7 +424,14 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
     const int koff = lane * 8, voff = qd * (4 * D) + n * 4;
     {
         const taper_work_item item = a.items[it];
-        const int32_t* __restrict__ row = a.bt + (int64_t)item.seq0 * a.bt_stride + item.page0;
+        typedef const __attribute__((address_space(4))) int32_t* scalar_row;
+        typedef const int32_t* __restrict__ vector_row;
+        typename std::conditional<SB, scalar_row, vector_row>::type row;
+        if constexpr (SB)
+            row = (scalar_row)(a.bt + (int64_t)__builtin_amdgcn_readfirstlane(item.seq0) * a.bt_stride +
+                               __builtin_amdgcn_readfirstlane(item.page0));
+        else
+            row = a.bt + (int64_t)item.seq0 * a.bt_stride + item.page0;
         const int n_tok = item.n_tokens;
         const int n_pages = (n_tok + 15) >> 4;
         const int n_blocks = (n_tok + 31) >> 5;
@@ -572,7 +586,7 @@ DEV void private_item(const StepArgs& a, const int it, const int hk, PrivateSmem
 // can take from its kv head's pool.  Every workgroup makes exactly one claim past the end of
 // the pool; the one that makes the last of those puts the counter back to zero for the next
 // launch.
-template <int D, int PF>
+template <int D, int PF, bool SB>
 DEV void private_items(const StepArgs& a, int it0, const int it1, const int hk, PrivateSmem<D>& sm) {
     const int wgs_per_head = a.n_parts_shared + a.n_parts_private;  // = gridDim.x / n_kv_heads
 #ifdef TAPER_WG_TRACE
@@ -603,12 +617,12 @@ DEV void private_items(const StepArgs& a, int it0, const int it1, const int hk, 
             int end = it + 1;
             while (end < it1 && a.items[end].kind == 3) ++end;
             const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-            for (int k = it + wave; k < end; k += 4) private_item<D, true, PF>(a, k, hk, sm);
+            for (int k = it + wave; k < end; k += 4) private_item<D, true, PF, SB>(a, k, hk, sm);
             it0 = end;
             __syncthreads();
             continue;
         }
-        private_item<D, false, PF>(a, it, hk, sm);
+        private_item<D, false, PF, SB>(a, it, hk, sm);
     }
 }
 
@@ -1070,7 +1084,8 @@ DEV void shared_path_wide(const StepArgs& a, const int part, const int hk, Share
 // One launch per layer: workgroup (share, kv head).  Shares below n_parts_shared
 // stream shared prefixes, the others private tokens; both kinds run side by side.
 // ---------------------------------------------------------------------------
-template <int D, int NTW, int PF>
+// ALLP: a launch without shared-prefix work (no shared path in the kernel, block-table rows by scalar loads).
+template <int D, int NTW, int PF, bool ALLP>
 __global__ __launch_bounds__(256, (NTW <= 2 || D == 128 ? 2 : 1)) void decode_kernel(StepArgs a) {
     union Smem {
         SharedSmem<D> sh;
@@ -1084,7 +1099,10 @@ __global__ __launch_bounds__(256, (NTW <= 2 || D == 128 ? 2 : 1)) void decode_ke
     if (threadIdx.x == 0 && trace) trace[4 * blockIdx.x] = wall_clock64();
 #endif
     int it0 = 0, it1 = 0;  // private items of this workgroup's share
-    if (part < a.n_parts_shared) {
+    if constexpr (ALLP) {
+        it0 = a.part_start[part];
+        it1 = a.part_start[part + 1];
+    } else if (part < a.n_parts_shared) {
         if constexpr (NTW == 3 && D == 128)
             shared_path_wide<D, PF>(a, part, hk, *reinterpret_cast<SharedSmem<D>*>(smem_raw));
         else
@@ -1097,7 +1115,7 @@ __global__ __launch_bounds__(256, (NTW <= 2 || D == 128 ? 2 : 1)) void decode_ke
 #ifdef TAPER_WG_TRACE
     if (threadIdx.x == 0 && trace) trace[4 * blockIdx.x + 1] = wall_clock64();  // shared share done (a private share: overwritten when it is done)
 #endif
-    private_items<D, PF>(a, it0, it1, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
+    private_items<D, PF, ALLP>(a, it0, it1, hk, *reinterpret_cast<PrivateSmem<D>*>(smem_raw));
 #ifdef TAPER_WG_TRACE
     if (threadIdx.x == 0 && trace) trace[4 * blockIdx.x + 2] = wall_clock64();
 #endif
@@ -1194,9 +1212,10 @@ hipError_t launch_stream_read(const void* base, int64_t pieces_per_wg, int n_wor
 template <int D, int PF>
 static hipError_t launch_decode_as(const StepArgs& a, const dim3 grid, const int ntw, hipStream_t s) {
     const dim3 block(256);
-    if (ntw <= 1) hipLaunchKernelGGL((decode_kernel<D, 1, PF>), grid, block, 0, s, a);
-    else if (ntw == 2) hipLaunchKernelGGL((decode_kernel<D, 2, PF>), grid, block, 0, s, a);
-    else if (ntw == 3) hipLaunchKernelGGL((decode_kernel<D, 3, PF>), grid, block, 0, s, a);
+    if (a.n_parts_shared == 0) hipLaunchKernelGGL((decode_kernel<D, 1, PF, true>), grid, block, 0, s, a);
+    else if (ntw <= 1) hipLaunchKernelGGL((decode_kernel<D, 1, PF, false>), grid, block, 0, s, a);
+    else if (ntw == 2) hipLaunchKernelGGL((decode_kernel<D, 2, PF, false>), grid, block, 0, s, a);
+    else if (ntw == 3) hipLaunchKernelGGL((decode_kernel<D, 3, PF, false>), grid, block, 0, s, a);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
